@@ -1,0 +1,210 @@
+"""Pins for the oracle's block wiring (MMDiT joint block, branch forward, SDXL stage block):
+structural invariants plus an independent assembly from torch CPU fp64 library routines.
+The block layout itself is a reading of the workload text (the paper treats the denoiser
+as a black box), so these pin the implementation of that reading, not the reading."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+from oracle import hyb_oracle as O
+from paper_2602_21760_amd import synth
+
+
+def T(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float64))
+
+
+def _tiny_cfg(**kw):
+    base = dict(blocks=2, hidden=128, heads=2, latent_hw=8, latent_c=4, n_txt=5, ctx_dim=32, batch=2)
+    base.update(kw)
+    return synth.scaled(synth.CFG1, **base)
+
+
+def _block_inputs(cfg, seed=0, scale_w=1.0):
+    rng = np.random.default_rng(seed)
+    w = synth.mmdit_block_weights(cfg, 0)
+    w = {s: {n: a * scale_w for n, a in w[s].items()} for s in w}
+    x_img = rng.standard_normal((cfg.batch, cfg.n_img, cfg.hidden))
+    x_txt = rng.standard_normal((cfg.batch, cfg.n_txt, cfg.hidden))
+    temb = rng.standard_normal((cfg.batch, cfg.hidden))
+    return x_img, x_txt, temb, w
+
+
+def _torch_block(x_img, x_txt, temb, w, heads):
+    """The same block assembled from torch library calls."""
+    xs = {"img": T(x_img), "txt": T(x_txt)}
+    D = xs["img"].shape[-1]
+    mods, qkv = {}, {}
+    for s in ("img", "txt"):
+        m = F.linear(F.silu(T(temb)), T(w[s]["ada_w"]), T(w[s]["ada_b"]))
+        mods[s] = m.chunk(6, dim=-1)
+        h = F.layer_norm(xs[s], (D,), eps=1e-6) * (1 + mods[s][1][:, None]) + mods[s][0][:, None]
+        y = F.linear(h, T(w[s]["qkv_w"]), T(w[s]["qkv_b"]))
+        B, N, _ = y.shape
+        qkv[s] = [p.reshape(B, N, heads, D // heads).transpose(1, 2) for p in y.chunk(3, dim=-1)]
+    q, k, v = (torch.cat([qkv["img"][i], qkv["txt"][i]], dim=2) for i in range(3))
+    o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(q.shape[0], q.shape[2], D)
+    Ni = xs["img"].shape[1]
+    outs = {}
+    for s, os_ in (("img", o[:, :Ni]), ("txt", o[:, Ni:])):
+        x = xs[s] + mods[s][2][:, None] * F.linear(os_, T(w[s]["out_w"]), T(w[s]["out_b"]))
+        h = F.layer_norm(x, (D,), eps=1e-6) * (1 + mods[s][4][:, None]) + mods[s][3][:, None]
+        m = F.linear(F.gelu(F.linear(h, T(w[s]["fc1_w"]), T(w[s]["fc1_b"])), approximate="tanh"),
+                     T(w[s]["fc2_w"]), T(w[s]["fc2_b"]))
+        outs[s] = (x + mods[s][5][:, None] * m).numpy()
+    return outs["img"], outs["txt"]
+
+
+def test_block_against_library_assembly():
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 1, scale_w=10.0)   # large weights: every path matters
+    a_img, a_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    r_img, r_txt = _torch_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_allclose(a_img, r_img, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(a_txt, r_txt, rtol=1e-10, atol=1e-11)
+    # the block is not a no-op at these scales
+    assert np.linalg.norm(a_img - x_img) / np.linalg.norm(x_img) > 0.05
+
+
+def test_block_zero_modulation_is_identity():
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 2)
+    for s in w:
+        w[s]["ada_w"] = np.zeros_like(w[s]["ada_w"])
+        w[s]["ada_b"] = np.zeros_like(w[s]["ada_b"])
+    a_img, a_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_array_equal(a_img, x_img)
+    np.testing.assert_array_equal(a_txt, x_txt)
+
+
+def test_block_plain_prenorm_special_case():
+    """shift = scale = 0 and gate = 1 reduces to a plain pre-LayerNorm transformer block."""
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 3, scale_w=8.0)
+    D = cfg.hidden
+    for s in w:
+        w[s]["ada_w"] = np.zeros_like(w[s]["ada_w"])
+        b = np.zeros(6 * D)
+        b[2 * D:3 * D] = 1.0
+        b[5 * D:6 * D] = 1.0
+        w[s]["ada_b"] = b
+    a_img, a_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    xs = {"img": T(x_img), "txt": T(x_txt)}
+    qkv = {}
+    for s in xs:
+        y = F.linear(F.layer_norm(xs[s], (D,), eps=1e-6), T(w[s]["qkv_w"]), T(w[s]["qkv_b"]))
+        B, N, _ = y.shape
+        qkv[s] = [p.reshape(B, N, cfg.heads, 64).transpose(1, 2) for p in y.chunk(3, dim=-1)]
+    q, k, v = (torch.cat([qkv["img"][i], qkv["txt"][i]], dim=2) for i in range(3))
+    o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(cfg.batch, -1, D)
+    for s, os_, got in (("img", o[:, :cfg.n_img], a_img), ("txt", o[:, cfg.n_img:], a_txt)):
+        x = xs[s] + F.linear(os_, T(w[s]["out_w"]), T(w[s]["out_b"]))
+        x = x + F.linear(F.gelu(F.linear(F.layer_norm(x, (D,), eps=1e-6), T(w[s]["fc1_w"]), T(w[s]["fc1_b"])),
+                                approximate="tanh"), T(w[s]["fc2_w"]), T(w[s]["fc2_b"]))
+        np.testing.assert_allclose(got, x.numpy(), rtol=1e-10, atol=1e-11)
+
+
+def test_block_zero_out_projection_removes_attention_path():
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 4, scale_w=5.0)
+    for s in w:
+        w[s]["out_w"] = np.zeros_like(w[s]["out_w"])
+        w[s]["out_b"] = np.zeros_like(w[s]["out_b"])
+    a_img, _ = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    # then the image stream no longer depends on the text stream at all
+    b_img, _ = O.mmdit_block(x_img, x_txt * 3.0 + 1.0, temb, w, cfg.heads)
+    np.testing.assert_array_equal(a_img, b_img)
+
+
+def test_block_identical_rows_give_identical_outputs_and_text_matters():
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 5, scale_w=10.0)
+    x_img[1], x_txt[1], temb[1] = x_img[0], x_txt[0], temb[0]
+    a_img, a_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_array_equal(a_img[0], a_img[1])
+    np.testing.assert_array_equal(a_txt[0], a_txt[1])
+    x_txt[1] = -x_txt[1]
+    b_img, _ = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_array_equal(b_img[0], a_img[0])          # samples do not mix
+    assert np.abs(b_img[1] - a_img[1]).max() > 1e-6            # text reaches the image stream
+
+
+def test_block_without_text_is_self_attention():
+    cfg = _tiny_cfg(n_txt=0)
+    x_img, x_txt, temb, w = _block_inputs(cfg, 6, scale_w=10.0)
+    assert x_txt.shape[1] == 0
+    a_img, a_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    r_img, _ = _torch_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_allclose(a_img, r_img, rtol=1e-10, atol=1e-11)
+    assert a_txt.shape == x_txt.shape
+
+
+def test_forward_shapes_and_final_layer_special_case():
+    cfg = _tiny_cfg(blocks=1)
+    P = synth.mmdit_globals(cfg)
+    lat, ctx_c, _ = synth.mmdit_inputs(cfg)
+    latent = np.stack([lat, lat])
+    ctx = np.stack([ctx_c, ctx_c])
+    t = np.array([0.5, 0.5])
+    w = synth.mmdit_block_weights(cfg, 0)
+    for s in w:   # identity block
+        w[s]["ada_w"] = np.zeros_like(w[s]["ada_w"])
+        w[s]["ada_b"] = np.zeros_like(w[s]["ada_b"])
+    P["f_ada_w"] = np.zeros_like(P["f_ada_w"])
+    P["f_ada_b"] = np.zeros_like(P["f_ada_b"])
+    v = O.mmdit_forward(latent, ctx, t, P, [w], cfg.heads, cfg.patch)
+    assert v.shape == latent.shape
+    # identity block + zero final modulation: v = unpatchify(W_f LN(W_pe patch + b + pos) + b_f)
+    tok = T(O.patchify(latent, cfg.patch))
+    x = F.linear(tok, T(P["pe_w"]), T(P["pe_b"])) + T(P["pos"])
+    y = F.linear(F.layer_norm(x, (cfg.hidden,), eps=1e-6), T(P["f_w"]), T(P["f_b"])).numpy()
+    np.testing.assert_allclose(v, O.unpatchify(y, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch), rtol=1e-11)
+    np.testing.assert_array_equal(v[0], v[1])
+
+
+def test_forward_depends_on_time_and_text():
+    cfg = _tiny_cfg(blocks=2)
+    P = {n: a * 10 for n, a in synth.mmdit_globals(cfg).items()}
+    blocks = [{s: {n: a * 10 for n, a in d.items()} for s, d in synth.mmdit_block_weights(cfg, i).items()}
+              for i in range(cfg.blocks)]
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    v1 = O.mmdit_forward(lat[None], ctx_c[None], np.array([0.5]), P, blocks, cfg.heads, cfg.patch)
+    v2 = O.mmdit_forward(lat[None], ctx_u[None], np.array([0.5]), P, blocks, cfg.heads, cfg.patch)
+    v3 = O.mmdit_forward(lat[None], ctx_c[None], np.array([0.45]), P, blocks, cfg.heads, cfg.patch)
+    assert np.abs(v1 - v2).max() > 1e-8 and np.abs(v1 - v3).max() > 1e-8
+    # batched evaluation equals per-sample evaluation
+    vb = O.mmdit_forward(np.stack([lat, lat]), np.stack([ctx_c, ctx_u]), np.array([0.5, 0.5]), P, blocks,
+                         cfg.heads, cfg.patch)
+    np.testing.assert_allclose(vb[0], v1[0], rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(vb[1], v2[0], rtol=1e-9, atol=1e-11)
+
+
+def test_sdxl_block_against_library_assembly():
+    cfg = synth.SDXLStageConfig("t", blocks=1, tokens=9, channels=128, heads=2, n_ctx=5, ctx_dim=48)
+    w = {n: (a * 8 if n.endswith("_w") else a) for n, a in synth.sdxl_block_weights(cfg, 0).items()}
+    x, ctx = synth.sdxl_inputs(cfg)
+    got = O.sdxl_block(x, ctx, w, cfg.heads)
+    C, H = cfg.channels, cfg.heads
+
+    def heads(y):
+        B, N, _ = y.shape
+        return y.reshape(B, N, H, C // H).transpose(1, 2)
+
+    def merge(o):
+        return o.transpose(1, 2).reshape(o.shape[0], o.shape[2], C)
+
+    xt, ct = T(x), T(ctx)
+    g = F.group_norm(xt.permute(0, 2, 1), 32, T(w["gn_g"]), T(w["gn_b"]), eps=1e-5).permute(0, 2, 1)
+    h = F.layer_norm(g, (C,), T(w["ln1_g"]), T(w["ln1_b"]), eps=1e-5)
+    o = F.scaled_dot_product_attention(heads(F.linear(h, T(w["q1_w"]))), heads(F.linear(h, T(w["k1_w"]))),
+                                       heads(F.linear(h, T(w["v1_w"]))))
+    a = g + F.linear(merge(o), T(w["o1_w"]), T(w["o1_b"]))
+    h = F.layer_norm(a, (C,), T(w["ln2_g"]), T(w["ln2_b"]), eps=1e-5)
+    o = F.scaled_dot_product_attention(heads(F.linear(h, T(w["q2_w"]))), heads(F.linear(ct, T(w["k2_w"]))),
+                                       heads(F.linear(ct, T(w["v2_w"]))))
+    b = a + F.linear(merge(o), T(w["o2_w"]), T(w["o2_b"]))
+    h = F.layer_norm(b, (C,), T(w["ln3_g"]), T(w["ln3_b"]), eps=1e-5)
+    u, gate = F.linear(h, T(w["ff1_w"]), T(w["ff1_b"])).chunk(2, dim=-1)
+    c = b + F.linear(u * F.gelu(gate), T(w["ff2_w"]), T(w["ff2_b"]))
+    np.testing.assert_allclose(got, (xt + c).numpy(), rtol=1e-10, atol=1e-11)
+    assert np.linalg.norm(got - x) / np.linalg.norm(x) > 0.05
