@@ -1,0 +1,204 @@
+/*
+ * hyb.h -- C ABI of libhyb: the per-step hot path of conditional-guidance hybrid
+ * parallelism for diffusion inference, for AMD MI355X (gfx950 / CDNA4).
+ *
+ * The paper partitions a guided denoising step by condition: the conditional and the
+ * unconditional evaluation of the denoiser f_theta are the two data-parallel units
+ * (Sec. 4.1), their outputs are merged by classifier-free guidance (Sec. 3), their
+ * relative discrepancy drives the adaptive switching (Sec. 4.2-4.3, Eq. 1-3, Alg. 1), and
+ * the scheduler advances the latent.  This library is one device's share of that step:
+ * the denoiser forward of one (or both, batched) guidance branches, the CFG combine, the
+ * discrepancy reduction and the Euler update.
+ *
+ * Conventions (all entry points):
+ *  - Every pointer named in a "device" argument is caller-owned GPU memory, contiguous,
+ *    row-major, 16-byte aligned.  The library never allocates, frees or retains it.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    enqueue work; they never synchronise.  Results that are scalars (discrepancies) are
+ *    written to device memory so that the call stays asynchronous.
+ *  - Return value: HYB_OK or an error code; on error nothing has been enqueued (except
+ *    HYB_ERR_LAUNCH, which reports a failed kernel launch).  hyb_last_error_string()
+ *    gives a thread-local description of the last error.
+ *  - dtype HYB_BF16: weights and GEMM/attention operands are bf16 (stored as 16-bit
+ *    words), accumulation, softmax, normalisation statistics, biases, modulation vectors
+ *    and the residual stream are fp32.  dtype HYB_F32: everything is fp32.
+ *  - Linear weights are stored [out_features, in_features] row-major; biases are fp32.
+ *  - Token tensors are token-major [batch, tokens, features].
+ *  - Results are deterministic and batch-invariant: a sample's result does not depend on
+ *    its batch index or on what else is in the batch (no floating-point atomics).
+ */
+#ifndef HYB_H
+#define HYB_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HYB_OK = 0,
+    HYB_ERR_NULL = 1,       /* a required pointer is NULL */
+    HYB_ERR_SHAPE = 2,      /* a size is negative, inconsistent or unsupported */
+    HYB_ERR_DTYPE = 3,      /* unknown or unsupported dtype / enum value */
+    HYB_ERR_ALIGN = 4,      /* a device pointer is not 16-byte aligned */
+    HYB_ERR_WORKSPACE = 5,  /* workspace missing or smaller than the *_workspace_bytes query */
+    HYB_ERR_LAUNCH = 6      /* the HIP runtime rejected a kernel launch */
+} hyb_status;
+
+typedef enum { HYB_F32 = 0, HYB_BF16 = 1 } hyb_dtype;
+
+/* HYB_NORM_L1: the paper's rel-MAE (Eq. 1).  HYB_NORM_L2: the relative-L2 variant. */
+typedef enum { HYB_NORM_L1 = 1, HYB_NORM_L2 = 2 } hyb_norm;
+
+typedef enum {
+    HYB_EPI_BIAS = 0,          /* out = a w^T + bias                                          */
+    HYB_EPI_GELU_TANH = 1,     /* out = GELUtanh(a w^T + bias)                                */
+    HYB_EPI_SILU = 2,          /* out = SiLU(a w^T + bias)                                    */
+    HYB_EPI_GATE_RESIDUAL = 3  /* out(fp32) = residual + gate[row / rows_per_gate] * (a w^T + bias) */
+} hyb_epilogue;
+
+int hyb_version(void);                       /* major * 10000 + minor * 100 + patch */
+const char* hyb_last_error_string(void);     /* never NULL; valid until the next call on this thread */
+
+/* ------------------------------------------------------------------------------------------
+ * Guidance step (Sec. 3 CFG equation; Eq. 1 and its velocity form in Sec. 4.2; Alg. 1 steps
+ * "M_t" and "Step Denoise"; flow ODE of Sec. 3).
+ * ---------------------------------------------------------------------------------------- */
+
+/* v_out[i] = v_u[i] + scale * (v_c[i] - v_u[i]), i < n.  `scale` = 1 + w of the paper's
+ * eps_c + w (eps_c - eps_u): scale 1 returns the conditional, 0 the unconditional prediction.
+ * v_c, v_u, v_out: device, n elements of `dtype`; v_out may alias v_c or v_u.  n == 0 is a no-op. */
+int hyb_cfg_combine(const void* v_c, const void* v_u, void* v_out, size_t n, float scale,
+                    hyb_dtype dtype, void* stream);
+
+/* out[b] = ||v_c[b] - v_u[b]||_p / ||v_u[b]||_p over the n_per_sample elements of sample b
+ * (one ratio per sample; 0/0 -> 0, x/0 -> +inf).  v_c, v_u: device [batch, n_per_sample] of
+ * `dtype`; out: device float[batch]; workspace: device, at least
+ * hyb_discrepancy_workspace_bytes(batch, n_per_sample) bytes, contents irrelevant.
+ * Sums are accumulated in a fixed order (fp32 within a thread, fp64 across threads). */
+int hyb_branch_discrepancy(const void* v_c, const void* v_u, int batch, size_t n_per_sample,
+                           hyb_norm p, hyb_dtype dtype, float* out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+size_t hyb_discrepancy_workspace_bytes(int batch, size_t n_per_sample);
+
+/* x_out[i] = x[i] + (t_next - t) * v[i], i < n: explicit Euler step of dx/dt = v.
+ * dt = t_next - t is formed once on the host in fp32, the update is one fused multiply-add.
+ * x, x_out: device, `x_dtype`; v: device, `v_dtype`; x_out may alias x. */
+int hyb_euler_step(const void* x, const void* v, void* x_out, size_t n, float t, float t_next,
+                   hyb_dtype x_dtype, hyb_dtype v_dtype, void* stream);
+
+/* The three calls above in ONE pass over HBM: reads v_c, v_u, x once; writes x_out (fp32),
+ * optionally x_out_lowp (bf16 copy of x_out for the next denoiser call) and v_out (`v_dtype`),
+ * and both discrepancies.  Layout [batch, n_per_sample]; x, x_out fp32; v_* of `v_dtype`.
+ * x_out may alias x.  x_out_lowp, v_out, disc_l1, disc_l2 may each be NULL (skipped).
+ * disc_l1 / disc_l2: device float[batch].  Workspace as for hyb_branch_discrepancy.
+ * Generalised update: x_out = a * x + b * v with (a, b) = (1, t_next - t); see hyb_cfg_disc_affine. */
+int hyb_cfg_disc_euler(const void* v_c, const void* v_u, const float* x, float* x_out,
+                       void* x_out_lowp, void* v_out, int batch, size_t n_per_sample,
+                       float scale, float t, float t_next, float* disc_l1, float* disc_l2,
+                       hyb_dtype v_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same pass with a generic affine scheduler update x_out = a * x + b * v_cfg (DDIM, the
+ * CFG-adjusted reverse mean of Sec. 3 and Euler (a = 1, b = dt) are all of this form). */
+int hyb_cfg_disc_affine(const void* v_c, const void* v_u, const float* x, float* x_out,
+                        void* x_out_lowp, void* v_out, int batch, size_t n_per_sample,
+                        float scale, float a, float b, float* disc_l1, float* disc_l2,
+                        hyb_dtype v_dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Denoiser f_theta(x_t, c, t) of one guidance branch (Sec. 4.1): building blocks.
+ * The paper treats f_theta as a black box; the block below is the joint image+text
+ * transformer block of the flow-matching model it evaluates (MMDiT layout).
+ * ---------------------------------------------------------------------------------------- */
+
+/* o = softmax(q k^T * scale) v per (batch, head).
+ * q: device [batch, heads, n_q, head_dim]; k, v: device [batch, heads, n_kv, head_dim];
+ * o: device [batch, n_q, heads * head_dim] (heads merged, feature = head * head_dim + i).
+ * For joint attention n_q = n_kv = n_img + n_txt with image tokens first; n_q != n_kv is
+ * cross-attention.  scale <= 0 means 1 / sqrt(head_dim).  head_dim must be 64.
+ * n_q == 0 or batch == 0 is a no-op; n_kv == 0 with n_q > 0 is HYB_ERR_SHAPE. */
+int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
+                        int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
+                        hyb_dtype dtype, void* stream);
+
+/* out[b, r] = sum_k w[r, k] * SiLU(temb[b, k]) + bias[r]: the adaLN modulation vectors of any
+ * number of blocks / streams at once (stack their weight matrices along rows).
+ * w: device [rows, hidden] of `dtype`; bias: device float[rows]; temb: device float[batch, hidden];
+ * out: device float[batch, rows].  hidden % 8 == 0. */
+int hyb_adaln_modulation(const void* w, const float* bias, const float* temb, float* out,
+                         int rows, int hidden, int batch, hyb_dtype dtype, void* stream);
+
+/* out[b, n, :] = LN(x[b, n, :]) * (1 + scale[b, :]) + shift[b, :], LN over the feature axis with
+ * biased variance and no affine.  x: device float[batch, tokens, hidden]; shift, scale: device
+ * float, element (b, j) at shift[b * mod_stride + j]; out: device [batch, tokens, hidden] of
+ * `out_dtype`.  shift == scale == NULL gives the plain LayerNorm.  hidden % 4 == 0, <= 8192. */
+int hyb_layernorm_modulate(const float* x, const float* shift, const float* scale, size_t mod_stride,
+                           void* out, int batch, int tokens, int hidden, float eps,
+                           hyb_dtype out_dtype, void* stream);
+
+/* out = epilogue(a w^T + bias).  a: device [m, k] of `dtype`; w: device [n, k] of `dtype`;
+ * bias: device float[n] or NULL; out: device [m, n] of `out_dtype` (fp32 required for
+ * HYB_EPI_GATE_RESIDUAL).  residual: device float[m, n] (may alias out); gate: device float,
+ * element (row r, column j) at gate[(r / rows_per_gate) * gate_stride + j], or NULL for gate 1.
+ * k % 8 == 0 and n % 8 == 0 for bf16.  m == 0 is a no-op. */
+int hyb_linear(const void* a, const void* w, const float* bias, void* out, int m, int n, int k,
+               hyb_dtype dtype, hyb_dtype out_dtype, hyb_epilogue epi,
+               const float* residual, const float* gate, int rows_per_gate, size_t gate_stride,
+               void* stream);
+
+typedef struct {
+    int batch;        /* samples (1 = one guidance branch, 2 = conditional + unconditional) */
+    int n_img;        /* image tokens per sample */
+    int n_txt;        /* text tokens per sample (may be 0) */
+    int hidden;       /* D = heads * head_dim */
+    int heads;
+    int head_dim;     /* must be 64 */
+    int mlp_ratio;    /* MLP inner width = mlp_ratio * hidden */
+    hyb_dtype dtype;
+    float ln_eps;     /* 1e-6 for the MMDiT block */
+} hyb_block_desc;
+
+typedef struct {
+    const void *w_qkv, *w_out, *w_fc1, *w_fc2;        /* [3D, D], [D, D], [rD, D], [D, rD] of dtype */
+    const float *b_qkv, *b_out, *b_fc1, *b_fc2;       /* fp32 */
+} hyb_stream_weights;
+
+typedef struct { hyb_stream_weights img, txt; } hyb_block_weights;
+
+/* One joint block.  For each stream s in {img, txt} with modulation vectors
+ * (shift1, scale1, gate1, shift2, scale2, gate2) = the six hidden-sized chunks of mod_s[b, :]:
+ *   h = LN(x_s)(1 + scale1) + shift1;  q, k, v = split3(h Wqkv^T + b), heads of 64 features
+ *   o = softmax(Q K^T / 8) V over the concatenated (image first) tokens of both streams
+ *   x_s += gate1 * (o_s Wout^T + b);   h2 = LN(x_s)(1 + scale2) + shift2
+ *   x_s += gate2 * (GELUtanh(h2 W1^T + b1) W2^T + b2)
+ * x_img_in / x_img_out: device float[batch, n_img, hidden]; x_txt_*: device float[batch, n_txt,
+ * hidden]; outputs may alias inputs.  mod_img, mod_txt: device float[batch, 6 * hidden] with row
+ * stride mod_stride (from hyb_adaln_modulation).  workspace: device,
+ * >= hyb_block_workspace_bytes(desc) bytes. */
+int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_weights* weights,
+                      const float* x_img_in, const float* x_txt_in,
+                      const float* mod_img, const float* mod_txt, size_t mod_stride,
+                      float* x_img_out, float* x_txt_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+size_t hyb_block_workspace_bytes(const hyb_block_desc* desc);
+
+/* Sinusoidal timestep features: out[b, j] = cos(1000 t[b] f_j), out[b, dim/2 + j] = sin(1000 t[b] f_j),
+ * f_j = exp(-ln(10000) j / (dim/2)).  t: device float[batch]; out: device [batch, dim] of `out_dtype`. */
+int hyb_timestep_embedding(const float* t, void* out, int batch, int dim, hyb_dtype out_dtype, void* stream);
+
+/* latent[batch, hh, ww, c] (channels last, fp32) -> tokens[batch, (hh/p)(ww/p), p*p*c] of `out_dtype`,
+ * patch vector ordered (dy, dx, c); hyb_unpatchify is the inverse (tokens of `in_dtype` -> out of
+ * `out_dtype`). */
+int hyb_patchify(const float* latent, void* tokens, int batch, int hh, int ww, int c, int p,
+                 hyb_dtype out_dtype, void* stream);
+int hyb_unpatchify(const void* tokens, void* latent, int batch, int hh, int ww, int c, int p,
+                   hyb_dtype in_dtype, hyb_dtype out_dtype, void* stream);
+
+/* Element-wise conversion fp32 -> `out_dtype` (n elements), e.g. context tokens to bf16. */
+int hyb_convert(const float* in, void* out, size_t n, hyb_dtype out_dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYB_H */

@@ -1,0 +1,21 @@
+// Internal attention interface of libhyb: o = softmax(q k^T * scale) v per (batch, head), head_dim 64.
+#pragma once
+#include "common.h"
+
+struct AttnArgs {
+    const void* q;   // [batch, heads, n_q, 64]
+    const void* k;   // [batch, heads, n_kv, 64]
+    const void* v;   // [batch, heads, n_kv, 64]
+    void* o;         // [batch, split, heads * 64]: query rows [0, split)
+    void* o2;        // [batch, n_q - split, heads * 64]: query rows [split, n_q) (joint attention hands the
+                     // image and text rows back to their own streams); nullptr when split == n_q
+    int split;
+    int batch, heads, n_q, n_kv;
+    float scale;     // > 0
+};
+
+// Plain kernel (fp32 or bf16 storage, fp32 math with accurate expf).
+int hyb_launch_attention_simple(const AttnArgs& a, hyb_dtype dtype, hipStream_t st);
+// bf16 flash-style MFMA kernel.
+int hyb_launch_attention_mfma(const AttnArgs& a, hipStream_t st);
+int hyb_launch_attention(const AttnArgs& a, hyb_dtype dtype, hipStream_t st);

@@ -1,0 +1,73 @@
+// Shared host/device helpers of libhyb (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+
+#include "../../include/hyb.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+#define HYB_WAVE 64
+
+// ---- error reporting -----------------------------------------------------------------------
+int hyb_set_error(int code, const char* fmt, ...);
+
+#define HYB_REQUIRE(cond, code, ...)                         \
+    do {                                                     \
+        if (!(cond)) return hyb_set_error((code), __VA_ARGS__); \
+    } while (0)
+
+#define HYB_CHECK_PTR(p) HYB_REQUIRE((p) != nullptr, HYB_ERR_NULL, "%s: argument '%s' is NULL", __func__, #p)
+#define HYB_CHECK_ALIGN(p) \
+    HYB_REQUIRE((((uintptr_t)(p)) & 15u) == 0, HYB_ERR_ALIGN, "%s: argument '%s' is not 16-byte aligned", __func__, #p)
+#define HYB_CHECK_DTYPE(d) \
+    HYB_REQUIRE((d) == HYB_F32 || (d) == HYB_BF16, HYB_ERR_DTYPE, "%s: argument '%s' is not a valid dtype", __func__, #d)
+
+int hyb_check_launch(const char* what);
+
+static inline size_t hyb_dtype_size(hyb_dtype d) { return d == HYB_BF16 ? 2 : 4; }
+static inline size_t hyb_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- device helpers ------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short u) { return __uint_as_float(((unsigned int)u) << 16); }
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float gelu_tanh_f(float z) {
+    // 0.5 z (1 + tanh(u)) = z * sigmoid(2u), u = sqrt(2/pi) (z + 0.044715 z^3)
+    const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
+    return z / (1.0f + __expf(-2.0f * u));
+}
+__device__ __forceinline__ float gelu_erf_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.7071067811865476f)); }

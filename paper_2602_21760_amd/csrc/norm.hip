@@ -1,0 +1,338 @@
+// Bandwidth-bound pieces of the denoiser forward: LayerNorm + adaLN modulate, the adaLN
+// modulation GEMV, GroupNorm, timestep features, patchify / unpatchify, dtype conversion.
+// (The denoiser f_theta is a black box in the paper, Sec. 4.1; these are the parts of the
+// transformer block around the contractions.)
+#include "common.h"
+
+#include <type_traits>
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// LayerNorm (+ modulate / affine).  One wave per row; the row lives in registers (hidden <=
+// 2048), statistics are two-pass in fp32 with wavefront-shuffle reductions.
+//   AFFINE = false: out = xhat * (1 + scale[b]) + shift[b]   (adaLN; shift/scale may be NULL)
+//   AFFINE = true : out = xhat * scale + shift               (gamma / beta per feature)
+// ------------------------------------------------------------------------------------------
+constexpr int kLnMaxVec = 8;   // float4 per lane -> hidden <= 8 * 64 * 4 = 2048
+
+template <typename OT, bool AFFINE>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, const float* __restrict__ shift,
+                                                        const float* __restrict__ scale, size_t mod_stride,
+                                                        OT* __restrict__ out, int rows, int tokens, int hidden, float eps) {
+    const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
+    const int row = blockIdx.x * 4 + wave;
+    if (row >= rows) return;
+    const int nvec = hidden / 4;
+    const f32x4* xr = reinterpret_cast<const f32x4*>(x + (size_t)row * hidden);
+    f32x4 r[kLnMaxVec];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < kLnMaxVec; i++) {
+        const int c = lane + i * HYB_WAVE;
+        if (c < nvec) {
+            r[i] = xr[c];
+            s += (r[i][0] + r[i][1]) + (r[i][2] + r[i][3]);
+        }
+    }
+    const float mean = wave_sum(s) / (float)hidden;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < kLnMaxVec; i++) {
+        const int c = lane + i * HYB_WAVE;
+        if (c < nvec) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float d = r[i][j] - mean;
+                q = fmaf(d, d, q);
+            }
+        }
+    }
+    const float rstd = rsqrtf(wave_sum(q) / (float)hidden + eps);
+    const size_t b = (size_t)(row / tokens);
+    const f32x4* sh = shift ? reinterpret_cast<const f32x4*>(shift + (AFFINE ? 0 : b * mod_stride)) : nullptr;
+    const f32x4* sc = scale ? reinterpret_cast<const f32x4*>(scale + (AFFINE ? 0 : b * mod_stride)) : nullptr;
+    OT* orow = out + (size_t)row * hidden;
+#pragma unroll
+    for (int i = 0; i < kLnMaxVec; i++) {
+        const int c = lane + i * HYB_WAVE;
+        if (c < nvec) {
+            f32x4 y;
+            const f32x4 a = sc ? sc[c] : (f32x4){0.f, 0.f, 0.f, 0.f};
+            const f32x4 bb = sh ? sh[c] : (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const float xh = (r[i][j] - mean) * rstd;
+                const float g = AFFINE ? (sc ? a[j] : 1.f) : 1.f + a[j];
+                y[j] = fmaf(xh, g, bb[j]);
+            }
+            if constexpr (sizeof(OT) == 4) {
+                *reinterpret_cast<f32x4*>(orow + 4 * c) = y;
+            } else {
+                bf16x4 o = {(bf16_t)y[0], (bf16_t)y[1], (bf16_t)y[2], (bf16_t)y[3]};
+                *reinterpret_cast<bf16x4*>(orow + 4 * c) = o;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// adaLN modulation GEMV: out[b, r] = sum_k w[r, k] SiLU(temb[b, k]) + bias[r].  Weight-read bound:
+// one wave per row streams the row with 16-byte loads; SiLU(temb) of up to kAdaMaxBatch samples
+// sits in LDS.
+// ------------------------------------------------------------------------------------------
+constexpr int kAdaMaxBatch = 4;
+constexpr int kAdaRowsPerWave = 4;
+
+template <typename WT> __device__ __forceinline__ void load8(const WT* p, float* r);
+template <> __device__ __forceinline__ void load8<float>(const float* p, float* r) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+    r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3]; r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
+}
+template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float* r) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; i++) r[i] = (float)a[i];
+}
+
+template <typename WT>
+__global__ __launch_bounds__(256) void adaln_kernel(const WT* __restrict__ w, const float* __restrict__ bias,
+                                                    const float* __restrict__ temb, float* __restrict__ out, int rows,
+                                                    int hidden, int batch, int out_stride) {
+    extern __shared__ float s_act[];   // [batch][hidden]
+    for (int i = threadIdx.x; i < batch * hidden; i += blockDim.x) s_act[i] = silu_f(temb[i]);
+    __syncthreads();
+    const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
+    const int row0 = (blockIdx.x * 4 + wave) * kAdaRowsPerWave;
+    float acc[kAdaRowsPerWave][kAdaMaxBatch];
+#pragma unroll
+    for (int r = 0; r < kAdaRowsPerWave; r++)
+#pragma unroll
+        for (int b = 0; b < kAdaMaxBatch; b++) acc[r][b] = 0.f;
+    for (int k = lane * 8; k < hidden; k += HYB_WAVE * 8) {
+        float wv[kAdaRowsPerWave][8];
+#pragma unroll
+        for (int r = 0; r < kAdaRowsPerWave; r++) {
+            const int row = min(row0 + r, rows - 1);
+            load8<WT>(w + (size_t)row * hidden + k, wv[r]);
+        }
+#pragma unroll
+        for (int b = 0; b < kAdaMaxBatch; b++) {
+            if (b < batch) {
+                const float* a = s_act + b * hidden + k;
+#pragma unroll
+                for (int r = 0; r < kAdaRowsPerWave; r++)
+#pragma unroll
+                    for (int j = 0; j < 8; j++) acc[r][b] = fmaf(wv[r][j], a[j], acc[r][b]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kAdaRowsPerWave; r++)
+#pragma unroll
+        for (int b = 0; b < kAdaMaxBatch; b++) {
+            const float t = wave_sum(acc[r][b]);
+            if (lane == 0 && b < batch && row0 + r < rows) out[(size_t)b * out_stride + row0 + r] = t + bias[row0 + r];
+        }
+}
+
+// ------------------------------------------------------------------------------------------
+// GroupNorm on token-major data x[B, T, C]: one workgroup per (sample, group) computes the
+// statistics over (T, C/G) in two passes (fp32 per thread, fp64 across threads), then normalises.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void groupnorm_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
+                                                        const float* __restrict__ beta, float* __restrict__ out,
+                                                        int tokens, int channels, int groups, float eps) {
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int cg = channels / groups;
+    const float* xb = x + (size_t)b * tokens * channels + g * cg;
+    float* ob = out + (size_t)b * tokens * channels + g * cg;
+    const int n = tokens * cg;
+    __shared__ double red[4];
+    __shared__ float stat[2];
+    const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
+    float s = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) s += xb[(size_t)(i / cg) * channels + i % cg];
+    double ws = wave_sum((double)s);
+    if (lane == 0) red[wave] = ws;
+    __syncthreads();
+    if (threadIdx.x == 0) stat[0] = (float)(((red[0] + red[1]) + (red[2] + red[3])) / n);
+    __syncthreads();
+    const float mean = stat[0];
+    float q = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const float d = xb[(size_t)(i / cg) * channels + i % cg] - mean;
+        q = fmaf(d, d, q);
+    }
+    ws = wave_sum((double)q);
+    if (lane == 0) red[wave] = ws;
+    __syncthreads();
+    if (threadIdx.x == 0) stat[1] = (float)(1.0 / sqrt(((red[0] + red[1]) + (red[2] + red[3])) / n + (double)eps));
+    __syncthreads();
+    const float rstd = stat[1];
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const int c = i % cg;
+        const size_t o = (size_t)(i / cg) * channels + c;
+        ob[o] = fmaf((xb[o] - mean) * rstd, gamma[g * cg + c], beta[g * cg + c]);
+    }
+}
+
+template <typename OT>
+__global__ void timestep_embedding_kernel(const float* t, OT* out, int batch, int dim) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= batch * dim) return;
+    const int b = i / dim, j = i % dim, half = dim / 2;
+    const int f = j < half ? j : j - half;
+    const double ang = 1000.0 * (double)t[b] * exp(-9.210340371976184 * (double)f / (double)half);  // ln(10000)
+    out[i] = from_f32<OT>((float)(j < half ? cos(ang) : sin(ang)));
+}
+
+// tokens[b, py*(ww/p)+px, (dy*p+dx)*c + ch] = latent[b, py*p+dy, px*p+dx, ch]
+template <typename TT, typename LT, bool TO_TOKENS>
+__global__ void patch_kernel(LT* latent, TT* tokens, int batch, int hh, int ww, int c, int p) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)batch * hh * ww * c;
+    if (i >= total) return;
+    const int ch = i % c;
+    size_t r = i / c;
+    const int xw = r % ww; r /= ww;
+    const int yh = r % hh;
+    const size_t b = r / hh;
+    const int py = yh / p, dy = yh % p, px = xw / p, dx = xw % p;
+    const size_t tok = (b * (hh / p) + py) * (ww / p) + px;
+    const size_t ti = tok * ((size_t)p * p * c) + (size_t)(dy * p + dx) * c + ch;
+    using TV = std::remove_const_t<TT>;
+    using LV = std::remove_const_t<LT>;
+    if constexpr (TO_TOKENS) tokens[ti] = from_f32<TV>(to_f32<LV>(latent[i]));
+    else latent[i] = from_f32<LV>(to_f32<TV>(tokens[ti]));
+}
+
+template <typename OT>
+__global__ void convert_kernel(const float* in, OT* out, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = from_f32<OT>(in[i]);
+}
+
+}  // namespace
+
+// Internal launcher shared with the block composition (affine = gamma/beta LayerNorm).
+int hyb_launch_layernorm(const float* x, const float* shift, const float* scale, size_t mod_stride, void* out,
+                         int batch, int tokens, int hidden, float eps, hyb_dtype out_dtype, bool affine,
+                         hipStream_t st) {
+    const int rows = batch * tokens;
+    if (rows == 0) return HYB_OK;
+    dim3 grid((rows + 3) / 4), block(256);
+    if (out_dtype == HYB_F32) {
+        if (affine) hipLaunchKernelGGL((layernorm_kernel<float, true>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
+        else hipLaunchKernelGGL((layernorm_kernel<float, false>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
+    } else {
+        if (affine) hipLaunchKernelGGL((layernorm_kernel<bf16_t, true>), grid, block, 0, st, x, shift, scale, mod_stride, (bf16_t*)out, rows, tokens, hidden, eps);
+        else hipLaunchKernelGGL((layernorm_kernel<bf16_t, false>), grid, block, 0, st, x, shift, scale, mod_stride, (bf16_t*)out, rows, tokens, hidden, eps);
+    }
+    return hyb_check_launch("layernorm");
+}
+
+int hyb_launch_groupnorm(const float* x, const float* gamma, const float* beta, float* out, int batch, int tokens,
+                         int channels, int groups, float eps, hipStream_t st) {
+    if (batch == 0 || tokens == 0) return HYB_OK;
+    hipLaunchKernelGGL(groupnorm_kernel, dim3(groups, batch), dim3(256), 0, st, x, gamma, beta, out, tokens, channels, groups, eps);
+    return hyb_check_launch("groupnorm");
+}
+
+extern "C" int hyb_layernorm_modulate(const float* x, const float* shift, const float* scale, size_t mod_stride,
+                                      void* out, int batch, int tokens, int hidden, float eps,
+                                      hyb_dtype out_dtype, void* stream) {
+    HYB_CHECK_DTYPE(out_dtype);
+    HYB_REQUIRE(batch >= 0 && tokens >= 0, HYB_ERR_SHAPE, "hyb_layernorm_modulate: negative size");
+    HYB_REQUIRE(hidden > 0 && hidden % 4 == 0 && hidden <= kLnMaxVec * 256, HYB_ERR_SHAPE,
+                "hyb_layernorm_modulate: hidden %d must be a positive multiple of 4, at most %d", hidden, kLnMaxVec * 256);
+    if (batch == 0 || tokens == 0) return HYB_OK;
+    HYB_CHECK_PTR(x); HYB_CHECK_PTR(out);
+    HYB_CHECK_ALIGN(x); HYB_CHECK_ALIGN(out); HYB_CHECK_ALIGN(shift); HYB_CHECK_ALIGN(scale);
+    HYB_REQUIRE((shift == nullptr) == (scale == nullptr), HYB_ERR_NULL, "hyb_layernorm_modulate: shift and scale must both be given or both be NULL");
+    HYB_REQUIRE(mod_stride % 4 == 0, HYB_ERR_ALIGN, "hyb_layernorm_modulate: mod_stride must be a multiple of 4");
+    return hyb_launch_layernorm(x, shift, scale, mod_stride, out, batch, tokens, hidden, eps, out_dtype, false, (hipStream_t)stream);
+}
+
+extern "C" int hyb_adaln_modulation(const void* w, const float* bias, const float* temb, float* out,
+                                    int rows, int hidden, int batch, hyb_dtype dtype, void* stream) {
+    HYB_CHECK_DTYPE(dtype);
+    HYB_REQUIRE(rows >= 0 && batch >= 0, HYB_ERR_SHAPE, "hyb_adaln_modulation: negative size");
+    HYB_REQUIRE(hidden > 0 && hidden % 8 == 0 && hidden <= 4096, HYB_ERR_SHAPE,
+                "hyb_adaln_modulation: hidden %d must be a positive multiple of 8, at most 4096", hidden);
+    if (rows == 0 || batch == 0) return HYB_OK;
+    HYB_CHECK_PTR(w); HYB_CHECK_PTR(bias); HYB_CHECK_PTR(temb); HYB_CHECK_PTR(out);
+    HYB_CHECK_ALIGN(w); HYB_CHECK_ALIGN(bias); HYB_CHECK_ALIGN(temb); HYB_CHECK_ALIGN(out);
+    hipStream_t st = (hipStream_t)stream;
+    const int rows_per_block = 4 * kAdaRowsPerWave;
+    dim3 grid((rows + rows_per_block - 1) / rows_per_block), block(256);
+    for (int b0 = 0; b0 < batch; b0 += kAdaMaxBatch) {
+        const int nb = batch - b0 < kAdaMaxBatch ? batch - b0 : kAdaMaxBatch;
+        const size_t shmem = (size_t)nb * hidden * sizeof(float);
+        const float* tp = temb + (size_t)b0 * hidden;
+        float* op = out + (size_t)b0 * rows;
+        if (dtype == HYB_BF16) hipLaunchKernelGGL((adaln_kernel<bf16_t>), grid, block, shmem, st, (const bf16_t*)w, bias, tp, op, rows, hidden, nb, rows);
+        else hipLaunchKernelGGL((adaln_kernel<float>), grid, block, shmem, st, (const float*)w, bias, tp, op, rows, hidden, nb, rows);
+        int rc = hyb_check_launch("hyb_adaln_modulation");
+        if (rc != HYB_OK) return rc;
+    }
+    return HYB_OK;
+}
+
+extern "C" int hyb_timestep_embedding(const float* t, void* out, int batch, int dim, hyb_dtype out_dtype, void* stream) {
+    HYB_CHECK_DTYPE(out_dtype);
+    HYB_REQUIRE(batch >= 0 && dim > 0 && dim % 2 == 0, HYB_ERR_SHAPE, "hyb_timestep_embedding: batch >= 0 and an even dim > 0 required");
+    if (batch == 0) return HYB_OK;
+    HYB_CHECK_PTR(t); HYB_CHECK_PTR(out);
+    const int n = batch * dim;
+    if (out_dtype == HYB_F32) hipLaunchKernelGGL((timestep_embedding_kernel<float>), dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, t, (float*)out, batch, dim);
+    else hipLaunchKernelGGL((timestep_embedding_kernel<bf16_t>), dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, t, (bf16_t*)out, batch, dim);
+    return hyb_check_launch("hyb_timestep_embedding");
+}
+
+static int check_patch(const char* who, int batch, int hh, int ww, int c, int p) {
+    HYB_REQUIRE(batch >= 0 && hh >= 0 && ww >= 0 && c > 0 && p > 0, HYB_ERR_SHAPE, "%s: bad sizes", who);
+    HYB_REQUIRE(hh % p == 0 && ww % p == 0, HYB_ERR_SHAPE, "%s: latent %dx%d is not a multiple of patch %d", who, hh, ww, p);
+    return HYB_OK;
+}
+
+extern "C" int hyb_patchify(const float* latent, void* tokens, int batch, int hh, int ww, int c, int p,
+                            hyb_dtype out_dtype, void* stream) {
+    HYB_CHECK_DTYPE(out_dtype);
+    int rc = check_patch("hyb_patchify", batch, hh, ww, c, p);
+    if (rc) return rc;
+    const size_t n = (size_t)batch * hh * ww * c;
+    if (n == 0) return HYB_OK;
+    HYB_CHECK_PTR(latent); HYB_CHECK_PTR(tokens);
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (out_dtype == HYB_F32) hipLaunchKernelGGL((patch_kernel<float, const float, true>), grid, block, 0, (hipStream_t)stream, latent, (float*)tokens, batch, hh, ww, c, p);
+    else hipLaunchKernelGGL((patch_kernel<bf16_t, const float, true>), grid, block, 0, (hipStream_t)stream, latent, (bf16_t*)tokens, batch, hh, ww, c, p);
+    return hyb_check_launch("hyb_patchify");
+}
+
+extern "C" int hyb_unpatchify(const void* tokens, void* latent, int batch, int hh, int ww, int c, int p,
+                              hyb_dtype in_dtype, hyb_dtype out_dtype, void* stream) {
+    HYB_CHECK_DTYPE(in_dtype); HYB_CHECK_DTYPE(out_dtype);
+    int rc = check_patch("hyb_unpatchify", batch, hh, ww, c, p);
+    if (rc) return rc;
+    const size_t n = (size_t)batch * hh * ww * c;
+    if (n == 0) return HYB_OK;
+    HYB_CHECK_PTR(latent); HYB_CHECK_PTR(tokens);
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (in_dtype == HYB_F32 && out_dtype == HYB_F32) hipLaunchKernelGGL((patch_kernel<const float, float, false>), grid, block, 0, st, (float*)latent, (const float*)tokens, batch, hh, ww, c, p);
+    else if (in_dtype == HYB_F32) hipLaunchKernelGGL((patch_kernel<const float, bf16_t, false>), grid, block, 0, st, (bf16_t*)latent, (const float*)tokens, batch, hh, ww, c, p);
+    else if (out_dtype == HYB_F32) hipLaunchKernelGGL((patch_kernel<const bf16_t, float, false>), grid, block, 0, st, (float*)latent, (const bf16_t*)tokens, batch, hh, ww, c, p);
+    else hipLaunchKernelGGL((patch_kernel<const bf16_t, bf16_t, false>), grid, block, 0, st, (bf16_t*)latent, (const bf16_t*)tokens, batch, hh, ww, c, p);
+    return hyb_check_launch("hyb_unpatchify");
+}
+
+extern "C" int hyb_convert(const float* in, void* out, size_t n, hyb_dtype out_dtype, void* stream) {
+    HYB_CHECK_DTYPE(out_dtype);
+    if (n == 0) return HYB_OK;
+    HYB_CHECK_PTR(in); HYB_CHECK_PTR(out);
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    if (out_dtype == HYB_F32) hipLaunchKernelGGL((convert_kernel<float>), grid, block, 0, (hipStream_t)stream, in, (float*)out, n);
+    else hipLaunchKernelGGL((convert_kernel<bf16_t>), grid, block, 0, (hipStream_t)stream, in, (bf16_t*)out, n);
+    return hyb_check_launch("hyb_convert");
+}

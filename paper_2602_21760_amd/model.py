@@ -1,0 +1,128 @@
+"""Drivers that run the denoiser forward and the guided step purely through libhyb calls.
+
+This is marshalling only: weights are uploaded once (torch tensors = device memory), then every
+step of the path is a hyb_* call on torch's current stream.  No arithmetic of the method is done
+in Python or by torch operators."""
+import numpy as np
+import torch
+
+from . import binding as hb
+
+_TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def _dev(a, dtype=torch.float32):
+    """numpy float32 array -> device tensor (bf16 conversion is exact for bf16-representable data)."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t if dtype == torch.float32 else t.to(dtype)
+
+
+class MMDiT:
+    """Device-resident weights + workspaces of one MMDiT-shaped denoiser (see synth.MMDiTConfig)."""
+
+    def __init__(self, cfg, globals_np, blocks_iter, batch=None):
+        self.cfg = cfg
+        self.B = cfg.batch if batch is None else batch
+        self.act = _TORCH_DT[cfg.dtype]
+        self.hdt = hb.HYB_BF16 if cfg.dtype == "bf16" else hb.HYB_F32
+        D = cfg.hidden
+        P = globals_np
+        self.g = {n: _dev(P[n], self.act if n.endswith("_w") else torch.float32) for n in P if n != "pos"}
+        self.pos = _dev(P["pos"])
+        ada_w, ada_b, self.blocks, self._keep = [], [], [], []
+        for w in blocks_iter:
+            dev = {}
+            for s in ("img", "txt"):
+                dev[s] = {n: _dev(a, self.act if n.endswith("_w") else torch.float32) for n, a in w[s].items()
+                          if not n.startswith("ada_")}
+                ada_w.append(_dev(w[s]["ada_w"], self.act))
+                ada_b.append(_dev(w[s]["ada_b"]))
+            self._keep.append(dev)
+            self.blocks.append(hb.block_weights(dev["img"], dev["txt"]))
+        ada_w.append(self.g.pop("f_ada_w"))
+        ada_b.append(self.g.pop("f_ada_b"))
+        self.ada_w = torch.cat(ada_w, dim=0).contiguous()     # [(blocks * 2 * 6 + 2) * D, D]
+        self.ada_b = torch.cat(ada_b, dim=0).contiguous()
+        self.mod_rows = self.ada_w.shape[0]
+        self._alloc()
+
+    def _alloc(self):
+        cfg, B, D = self.cfg, self.B, self.cfg.hidden
+        f32 = dict(device="cuda", dtype=torch.float32)
+        act = dict(device="cuda", dtype=self.act)
+        self.desc = hb.block_desc(B, cfg.n_img, cfg.n_txt, D, cfg.heads, self.hdt, cfg.head_dim, cfg.mlp_ratio, 1e-6)
+        self.ws = torch.empty(max(hb.hyb_block_workspace_bytes(self.desc), 256), device="cuda", dtype=torch.uint8)
+        self.t_dev = torch.empty(B, **f32)
+        self.t_feat = torch.empty(B, cfg.temb_dim, **act)
+        self.t_hid = torch.empty(B, D, **act)
+        self.temb = torch.empty(B, D, **f32)
+        self.mod = torch.empty(B, self.mod_rows, **f32)
+        self.tok = torch.empty(B, cfg.n_img, cfg.patch_dim, **act)
+        self.ctx_act = torch.empty(B, cfg.n_txt, cfg.ctx_dim, **act)
+        self.x_img = torch.empty(B, cfg.n_img, D, **f32)
+        self.x_txt = torch.empty(B, cfg.n_txt, D, **f32)
+        self.y = torch.empty(B, cfg.n_img, D, **act)
+        self.out_tok = torch.empty(B, cfg.n_img, cfg.patch_dim, **act)
+        self.v = torch.empty(B, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, **act)
+
+    def embed(self, latent, ctx, t):
+        """latent: f32[B, Hh, Ww, C]; ctx: f32[B, Nt, ctx_dim]; t: f32[B] (device tensors)."""
+        cfg, g = self.cfg, self.g
+        hb.hyb_timestep_embedding(t, self.t_feat)
+        hb.hyb_linear(self.t_feat, g["t1_w"], g["t1_b"], self.t_hid, hb.HYB_EPI_SILU)
+        hb.hyb_linear(self.t_hid, g["t2_w"], g["t2_b"], self.temb, hb.HYB_EPI_BIAS)
+        hb.hyb_adaln_modulation(self.ada_w, self.ada_b, self.temb, self.mod)
+        hb.hyb_patchify(latent, self.tok, cfg.patch)
+        for b in range(self.B):    # the positional table is the "residual" of the patch projection
+            hb.hyb_linear(self.tok[b], g["pe_w"], g["pe_b"], self.x_img[b], hb.HYB_EPI_GATE_RESIDUAL, residual=self.pos)
+        if cfg.n_txt:
+            hb.hyb_convert(ctx, self.ctx_act)
+            hb.hyb_linear(self.ctx_act.view(-1, cfg.ctx_dim), g["ce_w"], g["ce_b"], self.x_txt.view(-1, cfg.hidden))
+
+    def run_blocks(self, first=0, last=None):
+        D = self.cfg.hidden
+        last = len(self.blocks) if last is None else last
+        for i in range(first, last):
+            mi = self.mod[:, (2 * i) * 6 * D:]
+            mt = self.mod[:, (2 * i + 1) * 6 * D:]
+            hb.hyb_block_forward(self.desc, self.blocks[i], self.x_img, self.x_txt, mi, mt, self.mod_rows,
+                                 self.x_img, self.x_txt, self.ws)
+
+    def final(self):
+        cfg, g, D = self.cfg, self.g, self.cfg.hidden
+        fo = len(self.blocks) * 2 * 6 * D
+        hb.hyb_layernorm_modulate(self.x_img, self.mod[:, fo:], self.mod[:, fo + D:], self.mod_rows, self.y, 1e-6)
+        hb.hyb_linear(self.y.view(-1, D), g["f_w"], g["f_b"], self.out_tok.view(-1, cfg.patch_dim))
+        hb.hyb_unpatchify(self.out_tok, self.v, cfg.patch)
+        return self.v
+
+    def forward(self, latent, ctx, t):
+        """One denoiser evaluation for every batch row; returns v[B, Hh, Ww, C] (activation dtype)."""
+        self.embed(latent, ctx, t)
+        self.run_blocks()
+        return self.final()
+
+
+class GuidedSampler:
+    """Both guidance branches as batch rows 0 (conditional) and 1 (unconditional) of one forward,
+    followed by the fused CFG / discrepancy / Euler pass; the latent master copy stays fp32."""
+
+    def __init__(self, model, scale):
+        assert model.B == 2
+        self.m, self.scale = model, scale
+        cfg = model.cfg
+        n = cfg.latent_elems
+        self.lat2 = torch.empty(2, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, device="cuda", dtype=torch.float32)
+        self.t2 = torch.empty(2, device="cuda", dtype=torch.float32)
+        self.ws = torch.empty(max(hb.hyb_discrepancy_workspace_bytes(1, n), 256), device="cuda", dtype=torch.uint8)
+        self.disc = torch.zeros(2, 64, device="cuda", dtype=torch.float32)   # [l1 | l2][step]
+
+    def step(self, x, ctx2, t, t_next, i=0):
+        """x: f32[Hh, Ww, C] master latent (updated in place); ctx2: f32[2, Nt, ctx_dim]."""
+        self.lat2[0].copy_(x)
+        self.lat2[1].copy_(x)
+        self.t2.fill_(t)
+        v = self.m.forward(self.lat2, ctx2, self.t2)
+        hb.hyb_cfg_disc_euler(v[0:1], v[1:2], x.view(1, -1), x.view(1, -1), self.scale, t, t_next,
+                              disc_l1=self.disc[0, i:i + 1], disc_l2=self.disc[1, i:i + 1], workspace=self.ws)
+        return x

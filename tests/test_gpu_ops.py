@@ -1,0 +1,146 @@
+"""GPU parity of the denoiser building blocks (linear + epilogues, LayerNorm-modulate, adaLN
+modulation, timestep features, patchify, attention) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hyb_oracle as O
+from paper_2602_21760_amd import synth
+from gpu_util import dev, host, rel_l2, tdt, tol
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2602_21760_amd import binding
+    binding.lib()
+    return binding
+
+
+def _data(seed, shape, dt, std=1.0):
+    return synth.normal(seed, shape, std, dt)
+
+
+# (m, n, k): ragged rows, several tiles, the real GEMM shapes' aspect; k a multiple of 64 for the MFMA
+# path, an odd k for the plain kernel (f32 only)
+LINEAR_SHAPES = [(1, 64, 64), (77, 128, 64), (333, 1536, 256), (300, 72, 128), (513, 384, 192)]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", LINEAR_SHAPES)
+def test_linear_epilogues(hb, dt, shape):
+    m, n, k = shape
+    a, w, b = _data(1, (m, k), dt), _data(2, (n, k), dt, 0.05), _data(3, (n,), "f32", 0.5)
+    da, dw, db = dev(a, tdt(dt)), dev(w, tdt(dt)), dev(b)
+    y = O.linear(a, w, b)
+    for epi, fn in ((hb.HYB_EPI_BIAS, lambda z: z), (hb.HYB_EPI_GELU_TANH, O.gelu_tanh), (hb.HYB_EPI_SILU, O.silu)):
+        for od in ("f32", dt):
+            out = torch.empty(m, n, device="cuda", dtype=tdt(od))
+            hb.hyb_linear(da, dw, db, out, epi)
+            assert rel_l2(host(out), fn(y)) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
+    # gate * y + residual with a per-sample gate (3 "samples" of ragged size) and without gate
+    rpg = (m + 2) // 3
+    res, gate = _data(4, (m, n), "f32"), _data(5, (3, 2 * n), "f32")
+    dres, dgate = dev(res), dev(gate)
+    out = torch.empty(m, n, device="cuda")
+    hb.hyb_linear(da, dw, db, out, hb.HYB_EPI_GATE_RESIDUAL, residual=dres, gate=dgate[:, n:], rows_per_gate=rpg,
+                  gate_stride=2 * n)
+    g_rows = gate[np.arange(m) // rpg, n:]
+    assert rel_l2(host(out), res + g_rows * y) < tol(dt)
+    hb.hyb_linear(da, dw, db, dres, hb.HYB_EPI_GATE_RESIDUAL, residual=dres)     # in place, gate = 1
+    assert rel_l2(host(dres), res + y) < tol(dt)
+    # no bias
+    out = torch.empty(m, n, device="cuda")
+    hb.hyb_linear(da, dw, None, out)
+    assert rel_l2(host(out), O.linear(a, w)) < tol(dt)
+
+
+def test_linear_odd_k_f32(hb):
+    m, n, k = 45, 37, 19
+    a, w, b = _data(1, (m, k), "f32"), _data(2, (n, k), "f32"), _data(3, (n,), "f32")
+    out = torch.empty(m, n, device="cuda")
+    hb.hyb_linear(dev(a), dev(w), dev(b), out)
+    assert rel_l2(host(out), O.linear(a, w, b)) < 1e-6
+
+
+@pytest.mark.parametrize("od", ["f32", "bf16"])
+@pytest.mark.parametrize("hidden", [256, 1536, 2048, 640])
+def test_layernorm_modulate(hb, od, hidden):
+    B, T = 2, 37
+    x = _data(10, (B, T, hidden), "f32") * 3 + 0.5
+    mod = _data(11, (B, 3 * hidden), "f32", 0.3)
+    dx, dmod = dev(x), dev(mod)
+    out = torch.empty(B, T, hidden, device="cuda", dtype=tdt(od))
+    hb.hyb_layernorm_modulate(dx, dmod[:, hidden:], dmod[:, 2 * hidden:], 3 * hidden, out, 1e-6)
+    ref = O.modulate(O.layer_norm(x, 1e-6), mod[:, hidden:2 * hidden], mod[:, 2 * hidden:])
+    assert rel_l2(host(out), ref) < (4e-3 if od == "bf16" else 1e-5)
+    hb.hyb_layernorm_modulate(dx, None, None, 0, out, 1e-6)
+    assert rel_l2(host(out), O.layer_norm(x, 1e-6)) < (4e-3 if od == "bf16" else 1e-5)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("batch", [1, 2, 5])
+def test_adaln_modulation(hb, dt, batch):
+    rows, hidden = 6 * 256 + 10, 256
+    w, b = _data(20, (rows, hidden), dt, 0.05), _data(21, (rows,), "f32")
+    temb = _data(22, (batch, hidden), "f32")
+    out = torch.empty(batch, rows, device="cuda")
+    hb.hyb_adaln_modulation(dev(w, tdt(dt)), dev(b), dev(temb), out)
+    assert rel_l2(host(out), O.linear(O.silu(temb), w, b)) < 1e-5
+
+
+def test_timestep_embedding_and_patchify(hb):
+    t = np.array([0.0, 0.5, 0.45, 1.0], dtype=np.float32)
+    out = torch.empty(4, 256, device="cuda")
+    hb.hyb_timestep_embedding(dev(t), out)
+    np.testing.assert_allclose(host(out), O.timestep_embedding(t, 256), atol=2e-7)
+    lat = _data(30, (2, 16, 12, 4), "f32")
+    tok = torch.empty(2, 8 * 6, 16, device="cuda")
+    hb.hyb_patchify(dev(lat), tok, 2)
+    np.testing.assert_array_equal(host(tok), O.patchify(lat, 2))
+    back = torch.empty(2, 16, 12, 4, device="cuda")
+    hb.hyb_unpatchify(tok, back, 2)
+    np.testing.assert_array_equal(host(back), lat.astype(np.float64))
+    tokb = torch.empty(2, 8 * 6, 16, device="cuda", dtype=torch.bfloat16)
+    hb.hyb_patchify(dev(lat), tokb, 2)
+    np.testing.assert_array_equal(host(tokb), O.patchify(synth.round_bf16(lat), 2))
+    c = torch.empty(2 * 16 * 12 * 4, device="cuda", dtype=torch.bfloat16)
+    hb.hyb_convert(dev(lat).view(-1), c)
+    np.testing.assert_array_equal(host(c), synth.round_bf16(lat).reshape(-1).astype(np.float64))
+
+
+# (batch, heads, n_q, n_kv): tiny, exactly one tile, tile + 1, ragged joint sizes (image + 333 text
+# tokens), cross-attention to 77 keys
+ATTN_SHAPES = [(1, 1, 1, 1), (2, 2, 64, 64), (1, 3, 65, 65), (2, 2, 80, 80), (1, 2, 461, 461), (2, 2, 200, 77),
+               (1, 1, 130, 333)]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ATTN_SHAPES)
+def test_attention(hb, dt, shape):
+    B, H, Nq, Nk = shape
+    q, k, v = _data(40, (B, H, Nq, 64), dt), _data(41, (B, H, Nk, 64), dt), _data(42, (B, H, Nk, 64), dt)
+    o = torch.empty(B, Nq, H * 64, device="cuda", dtype=tdt(dt))
+    hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o)
+    assert rel_l2(host(o), O.attention(q, k, v)) < (tol(dt) if dt == "f32" else 1e-2)
+    hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o, scale=0.3)
+    assert rel_l2(host(o), O.attention(q, k, v, scale=0.3)) < (tol(dt) if dt == "f32" else 1e-2)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_attention_invariants_on_gpu(hb, dt):
+    B, H, N = 1, 2, 150
+    q, v = _data(50, (B, H, N, 64), dt), _data(51, (B, H, N, 64), dt)
+    k = np.repeat(_data(52, (B, H, 1, 64), dt), N, axis=2)           # all keys equal -> mean of V
+    o = torch.empty(B, N, H * 64, device="cuda", dtype=tdt(dt))
+    hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o)
+    mean_v = np.concatenate([v[0, h].astype(np.float64).mean(0) for h in range(H)])
+    assert rel_l2(host(o)[0], np.broadcast_to(mean_v, (N, H * 64))) < (1e-5 if dt == "f32" else 1e-2)
+    # large logits: the streaming softmax must not overflow
+    qb = _data(53, (B, H, N, 64), dt) * 6
+    kb = _data(54, (B, H, N, 64), dt) * 6
+    hb.hyb_joint_attention(dev(qb, tdt(dt)), dev(kb, tdt(dt)), dev(v, tdt(dt)), o)
+    got = host(o)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 2e-2)
