@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on ONE MI355X: a "step" is one full denoiser forward of one guidance
+branch on the SD3-shaped 1024x1024 workload (24 joint blocks, hidden 1536, 4096 image + 333 text
+tokens, bf16), every kernel of the path included, inputs and weights resident in HBM.
+
+Prints one JSON line: the whole-step rate in TFLOP/s of algorithmic work and ms per step, a live
+per-kernel roofline for the dominant kernel (events recorded by the library around every launch),
+the fused guidance pass at its bandwidth-bound shape, and the CPU oracle timed on a bounded sample."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "ms per denoiser step + TFLOP/s (MFMA %), SD3-shaped MMDiT branch at 1024²"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def cpu_baseline(cfg, synth):
+    """The oracle, untuned, on the host cores: ONE of the 24 joint blocks at the full token count
+    (about 0.37 TFLOP of fp64 work), reported as TFLOP/s of the same algorithmic flop count."""
+    import numpy as np
+    from oracle import hyb_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count()
+    w = synth.mmdit_block_weights(cfg, 0)
+    x_img = synth.normal(101, (1, cfg.n_img, cfg.hidden), 1.0, "f32")
+    x_txt = synth.normal(102, (1, cfg.n_txt, cfg.hidden), 1.0, "f32")
+    temb = synth.normal(103, (1, cfg.hidden), 1.0, "f32")
+    t0 = time.time()
+    O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    dt = time.time() - t0
+    D, N = cfg.hidden, cfg.n_img + cfg.n_txt
+    flops = 24 * D * D * N + 4 * N * N * D + 24 * D * D
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1 of 24 joint blocks of the same workload (fp64 numpy), %.1f s" % dt,
+            "ms_per_step_extrapolated": dt * 1e3 * cfg.blocks}
+
+
+def guidance_roofline(hb, torch, steps):
+    """The fused CFG + discrepancy + Euler pass at its bandwidth-bound shape: 256 samples of 262144
+    latent elements (bf16 velocities, fp32 latent: 12 bytes per element, 805 MB per launch)."""
+    batch, n = 256, 262144
+    v_c = torch.randn(batch, n, device="cuda").to(torch.bfloat16)
+    v_u = torch.randn(batch, n, device="cuda").to(torch.bfloat16)
+    x = torch.randn(batch, n, device="cuda")
+    xo = torch.empty_like(x)
+    d1, d2 = torch.empty(batch, device="cuda"), torch.empty(batch, device="cuda")
+    ws = torch.empty(hb.hyb_discrepancy_workspace_bytes(batch, n), device="cuda", dtype=torch.uint8)
+    for _ in range(3):
+        hb.hyb_cfg_disc_euler(v_c, v_u, x, xo, 7.0, 0.5, 0.45, d1, d2, ws)
+    torch.cuda.synchronize()
+    hb.hyb_trace_enable(True)
+    for _ in range(steps):
+        hb.hyb_cfg_disc_euler(v_c, v_u, x, xo, 7.0, 0.5, 0.45, d1, d2, ws)
+    torch.cuda.synchronize()
+    tr = hb.hyb_trace_summary()["guidance_pass"]
+    hb.hyb_trace_enable(False)
+    us = tr["ms"] / tr["launches"] * 1e3
+    gbs = tr["work"] / tr["launches"] / (us * 1e-6) / 1e9
+    out = {"kernel": "guidance_pass", "shape": "batch 256 x 262144 elements", "bound": "hbm", "achieved": gbs,
+           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "us_per_launch": us,
+           "bytes_per_element": 12, "traffic": None}
+    # real latent shapes (latency-bound): time in microseconds
+    real = {}
+    for name, ne in (("sd3_1024", 262144), ("sd3_2048", 1048576), ("sdxl_1024", 65536)):
+        hb.hyb_trace_enable(True)
+        for _ in range(20):
+            flat = [a.view(-1)[:ne].view(1, -1) for a in (v_c, v_u, x, xo)]
+            hb.hyb_cfg_disc_euler(flat[0], flat[1], flat[2], flat[3], 7.0, 0.5, 0.45, d1[0:1], d2[0:1], ws)
+        torch.cuda.synchronize()
+        tr = hb.hyb_trace_summary()["guidance_pass"]
+        hb.hyb_trace_enable(False)
+        real[name] = round(tr["ms"] / tr["launches"] * 1e3, 2)
+    out["us_at_real_latent_shapes"] = real
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the two guidance branches are batched or run "
+              "back to back on it); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2602_21760_amd import binding as hb, model, synth
+
+    hb.lib()    # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CFG2
+    t0 = time.time()
+    m = model.MMDiT(cfg, synth.mmdit_globals(cfg), synth.mmdit_blocks(cfg))
+    lat, ctx_c, _ = synth.mmdit_inputs(cfg)
+    latent = torch.from_numpy(lat[None]).cuda()
+    ctx = torch.from_numpy(ctx_c[None]).cuda()
+    t = torch.full((1,), 0.5, device="cuda")
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    for _ in range(args.warmup):
+        m.forward(latent, ctx, t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m.forward(latent, ctx, t)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops = cfg.flops_per_sample() * cfg.batch
+    tflops = flops / (ms * 1e-3) / 1e12
+
+    # per-kernel timing of the same steps (events around every launch, recorded by the library)
+    hb.hyb_trace_enable(True)
+    for _ in range(args.steps):
+        m.forward(latent, ctx, t)
+    torch.cuda.synchronize()
+    trace = hb.hyb_trace_summary()
+    hb.hyb_trace_enable(False)
+    kernels = {}
+    for name, r in trace.items():
+        per = r["ms"] / r["launches"]
+        rate = r["work"] / r["launches"] / (per * 1e-3)
+        kernels[name] = {"launches_per_step": r["launches"] / args.steps, "ms_per_step": round(r["ms"] / args.steps, 4),
+                         "us_per_launch": round(per * 1e3, 2),
+                         ("tflops" if r["unit"] == "flop" else "gbs"): round(rate / (1e12 if r["unit"] == "flop" else 1e9), 1)}
+    flop_kernels = {k: v for k, v in trace.items() if v["unit"] == "flop"}
+    dom = max(flop_kernels, key=lambda k: flop_kernels[k]["ms"])
+    d = flop_kernels[dom]
+    ach = d["work"] / d["launches"] / (d["ms"] / d["launches"] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                "us_per_launch": d["ms"] / d["launches"] * 1e3, "flops_per_launch": d["work"] / d["launches"]}
+
+    guidance = guidance_roofline(hb, torch, max(args.steps, 10))
+    line = {
+        "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic", "mfma_frac_of_peak": tflops / PEAK_BF16_TFLOPS,
+        "config": {"workload": "configs[1]: SD3-shaped MMDiT branch, 1024x1024, 24 blocks, hidden 1536, "
+                               "4096+333 tokens, batch 1, one denoiser forward", "algorithmic_tflop_per_step": flops / 1e12},
+        "roofline": roofline, "guidance_pass_roofline": guidance, "kernels": kernels, "setup_s": round(setup_s, 1),
+        "device": torch.cuda.get_device_name(0),
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, synth)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -198,6 +198,17 @@ int hyb_unpatchify(const void* tokens, void* latent, int batch, int hh, int ww, 
 /* Element-wise conversion fp32 -> `out_dtype` (n elements), e.g. context tokens to bf16. */
 int hyb_convert(const float* in, void* out, size_t n, hyb_dtype out_dtype, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Optional per-launch timing, for benchmarks (callers that measure, not the paper's method).
+ * While enabled, every kernel launch of the library is bracketed by two events on its stream.
+ * hyb_trace_enable(1) clears earlier records.  hyb_trace_summary waits for the recorded events
+ * and writes one line per kernel: name <TAB> unit ("flop" | "byte") <TAB> launches <TAB>
+ * total milliseconds <TAB> total algorithmic work.  buf: HOST memory of `cap` bytes.
+ * Not thread-safe with respect to concurrent launches from other threads.
+ * ---------------------------------------------------------------------------------------- */
+int hyb_trace_enable(int on);
+int hyb_trace_summary(char* buf, size_t cap);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,8 @@ SIGNATURES = {
     "hyb_patchify": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "hyb_unpatchify": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp]),
     "hyb_convert": (_i, [_vp, _vp, _sz, _i, _vp]),
+    "hyb_trace_enable": (_i, [_i]),
+    "hyb_trace_summary": (_i, [C.c_char_p, _sz]),
 }
 
 _lib = None
@@ -241,4 +243,19 @@ def hyb_unpatchify(tokens, latent, p):
 
 def hyb_convert(src, out):
     _check(lib().hyb_convert(_p(src, torch.float32), _p(out), src.numel(), _dt(out), _stream()))
+    return out
+
+
+def hyb_trace_enable(on):
+    _check(lib().hyb_trace_enable(1 if on else 0))
+
+
+def hyb_trace_summary():
+    """-> {kernel name: {"unit", "launches", "ms", "work"}} for the launches recorded since tracing was enabled."""
+    buf = C.create_string_buffer(1 << 16)
+    _check(lib().hyb_trace_summary(buf, len(buf)))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, unit, count, ms, work = line.split("\t")
+        out[name] = {"unit": unit, "launches": int(count), "ms": float(ms), "work": float(work)}
     return out

@@ -165,6 +165,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
 
 int hyb_launch_attention_mfma(const AttnArgs& a, hipStream_t st) {
     dim3 grid((a.n_q + BQ - 1) / BQ, a.heads, a.batch), block(256);
+    HybTraceScope trace("attention_mfma", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
     hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, a);
     return hyb_check_launch("attention_mfma");
 }

@@ -54,6 +54,7 @@ __global__ __launch_bounds__(256) void attention_simple_kernel(AttnArgs a) {
 
 int hyb_launch_attention_simple(const AttnArgs& a, hyb_dtype dtype, hipStream_t st) {
     dim3 grid((a.n_q + 3) / 4, a.heads, a.batch), block(256);
+    HybTraceScope trace("attention_simple", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
     if (dtype == HYB_F32) hipLaunchKernelGGL((attention_simple_kernel<float>), grid, block, 0, st, a);
     else hipLaunchKernelGGL((attention_simple_kernel<bf16_t>), grid, block, 0, st, a);
     return hyb_check_launch("attention_simple");

@@ -34,6 +34,16 @@ int hyb_set_error(int code, const char* fmt, ...);
 
 int hyb_check_launch(const char* what);
 
+// ---- optional per-launch timing (hyb_trace_*) ----------------------------------------------
+// A scope object brackets one kernel launch with two events on the launch stream when tracing
+// is on; `work` is the algorithmic work of the launch (flops or bytes, `unit` says which).
+struct HybTraceScope {
+    int slot;
+    hipStream_t st;
+    HybTraceScope(const char* kernel, const char* unit, double work, hipStream_t stream);
+    ~HybTraceScope();
+};
+
 static inline size_t hyb_dtype_size(hyb_dtype d) { return d == HYB_BF16 ? 2 : 4; }
 static inline size_t hyb_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

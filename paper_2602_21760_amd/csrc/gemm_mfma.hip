@@ -171,6 +171,10 @@ int launch_tile(const GemmGroup& g, hipStream_t st) {
     const int tiles0 = ((g.p[0].m + T::BM - 1) / T::BM) * tiles_n;
     const int tiles1 = g.count > 1 ? ((g.p[1].m + T::BM - 1) / T::BM) * tiles_n : 0;
     if (tiles0 + tiles1 == 0) return HYB_OK;
+    char name[96];
+    snprintf(name, sizeof(name), "gemm_mfma_%dx%d.epi%d.n%d.k%d", T::BM, T::BN, EPI, g.n, g.k);
+    double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
+    HybTraceScope trace(name, "flop", 2.0 * rows * g.n * g.k, st);
     GemmGroup gg = g;
     if (tiles0 == 0) {  // keep problem 0 non-empty so that the tile -> problem split stays simple
         gg.p[0] = g.p[1];

@@ -77,6 +77,10 @@ int launch(const GemmGroup& g, int epi, hipStream_t st) {
     if (tiles_m0 + tiles_m1 == 0 || g.n == 0) return HYB_OK;
     dim3 grid((g.n + TS - 1) / TS, tiles_m0 + tiles_m1), block(256);
     HYB_REQUIRE(grid.y <= 65535, HYB_ERR_SHAPE, "gemm: too many row tiles (%u)", grid.y);
+    char name[96];
+    snprintf(name, sizeof(name), "gemm_simple.epi%d.n%d.k%d", epi, g.n, g.k);
+    double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
+    HybTraceScope trace(name, "flop", 2.0 * rows * g.n * g.k * (epi == EPI_GEGLU ? 2 : 1), st);
     if (epi == EPI_GEGLU) hipLaunchKernelGGL((gemm_simple_kernel<T, OT, true>), grid, block, 0, st, g, epi, tiles_m0);
     else hipLaunchKernelGGL((gemm_simple_kernel<T, OT, false>), grid, block, 0, st, g, epi, tiles_m0);
     return hyb_check_launch("gemm_simple");

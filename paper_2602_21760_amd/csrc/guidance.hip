@@ -163,6 +163,10 @@ int launch_guidance(const char* who, GuidanceArgs g, int batch, hyb_dtype vd, fl
     const int nblk = blocks_for(g.n, vec ? kVec : 1);
     HYB_REQUIRE(batch <= 65535, HYB_ERR_SHAPE, "%s: batch %d exceeds 65535", who, batch);
     dim3 grid(nblk, batch), block(kThreads);
+    // algorithmic bytes: v_c + v_u read, x read, x_out written, plus the optional outputs
+    const double vs = (double)hyb_dtype_size(vd);
+    const double per_elem = 2 * vs + (g.x_out ? 8 : 0) + (g.x_lowp ? 2 : 0) + (g.v_out ? vs : 0);
+    HybTraceScope trace("guidance_pass", "byte", per_elem * (double)batch * (double)g.n, st);
     if (vd == HYB_BF16) {
         if (vec) hipLaunchKernelGGL((guidance_kernel<bf16_t, 8>), grid, block, 0, st, g);
         else hipLaunchKernelGGL((guidance_kernel<bf16_t, 1>), grid, block, 0, st, g);

@@ -222,6 +222,7 @@ int hyb_launch_layernorm(const float* x, const float* shift, const float* scale,
     const int rows = batch * tokens;
     if (rows == 0) return HYB_OK;
     dim3 grid((rows + 3) / 4), block(256);
+    HybTraceScope trace("layernorm", "byte", (double)rows * hidden * (4 + hyb_dtype_size(out_dtype)), st);
     if (out_dtype == HYB_F32) {
         if (affine) hipLaunchKernelGGL((layernorm_kernel<float, true>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
         else hipLaunchKernelGGL((layernorm_kernel<float, false>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
@@ -266,6 +267,7 @@ extern "C" int hyb_adaln_modulation(const void* w, const float* bias, const floa
     hipStream_t st = (hipStream_t)stream;
     const int rows_per_block = 4 * kAdaRowsPerWave;
     dim3 grid((rows + rows_per_block - 1) / rows_per_block), block(256);
+    HybTraceScope trace("adaln_modulation", "byte", (double)rows * hidden * hyb_dtype_size(dtype) * ((batch + kAdaMaxBatch - 1) / kAdaMaxBatch), st);
     for (int b0 = 0; b0 < batch; b0 += kAdaMaxBatch) {
         const int nb = batch - b0 < kAdaMaxBatch ? batch - b0 : kAdaMaxBatch;
         const size_t shmem = (size_t)nb * hidden * sizeof(float);
