@@ -1,200 +1,223 @@
 // bf16 MFMA GEMM for gfx950: out = epilogue(A W^T + bias), A [m, k] tokens x features-in,
 // W [n, k] features-out x features-in, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
 //
-// Tiling: a workgroup of 4 waves (2 x 2) owns a BM x BN output tile (BM = 64 TM tokens,
-// BN = 64 TN features); each wave owns TM x TN MFMA tiles of 32 x 32.  The weight fragment is
-// the MFMA "A" operand and the token fragment the "B" operand, so that the 16 accumulator
-// registers of a lane run along the OUTPUT FEATURE axis (4 consecutive features per group of
-// 4 registers, one token per lane): bias / gate / residual / output are then moved as 8- or
-// 16-byte vectors.  Both operands are k-contiguous, so global -> LDS copies are 16-byte
-// vectors (8 lanes cover one 128-byte row of a 64-wide k slab), and LDS rows are padded by
-// 16 bytes so that the 16-byte fragment reads of 16 consecutive rows hit distinct banks.
-// The next k slab is fetched into registers while the current one is multiplied.
+// Tiling: a workgroup of 4 waves (2 x 2) owns a 128 x 128 output tile; each wave owns 2 x 2 MFMA
+// tiles of 32 x 32.  The weight fragment is the MFMA "A" operand and the token fragment the "B"
+// operand, so the 16 accumulator registers of a lane run along the output-feature axis (4
+// consecutive features per group of 4 registers, one token per lane).
+//
+// Main loop: k is cut into slabs of 64.  A slab of both operands (128 + 128 rows of 128 bytes) is
+// copied global -> LDS by 16-byte direct-to-LDS loads (global_load_lds_dwordx4: a wave fills 1 KB of
+// LDS per instruction, no VGPR staging, no ds_write), double buffered: the copy of slab s + 1 runs
+// while slab s is multiplied.  LDS rows are unpadded; the 16-byte slots of a row are XOR-swizzled
+// with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 16 consecutive rows hit distinct
+// banks (the swizzle is applied on the global side: each lane picks which 16 bytes it fetches).
+// Waits on the copies are explicit (s_waitcnt vmcnt + s_barrier); a full __syncthreads() would
+// force vmcnt(0) on every barrier through its fence.
+//
+// Epilogue: the accumulators (+ bias, activation, gate) are staged through LDS (reusing the slab
+// buffers) and written out row-contiguously, 16 bytes per lane, so that global stores and the
+// residual reads are whole 128-byte lines.  (Storing straight from the MFMA layout issues 8-byte
+// pieces to 32 different rows per instruction; at these sizes that made the epilogue cost a third
+// of the tile time.)
 //
 // Up to two problems with the same (n, k) share a launch (image and text stream of a joint
-// block).  Ragged edges: row / feature indices are clamped on load and masked on store.
-// The reduction order over k is fixed, and a token's result does not depend on which tile
-// row it falls in, so results are deterministic and batch-invariant.
+// block).  Ragged edges: row / feature indices are clamped on load and masked on store.  The
+// reduction order over k is fixed and a token's result does not depend on its tile row, so
+// results are deterministic and batch-invariant.
 #include "gemm.h"
 
 namespace {
 
-constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;   // bf16 elements per LDS row (144 bytes)
+constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int ROWB = BK * 2;                    // bytes per LDS row of a slab
+constexpr int STAGE_BYTES = (BM + BN) * ROWB;   // 32 KB
+constexpr int CPW = STAGE_BYTES / 1024 / 4;     // 1 KB chunks per wave per slab (8)
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES;     // 64 KB -> two workgroups per CU
+constexpr int OUT_STRIDE_B16 = BN * 2 + 16;     // staging row strides (bytes), padded against conflicts
+constexpr int OUT_STRIDE_F32 = BN * 4 + 16;
 
-template <int TM, int TN>
-struct Tile {
-    static constexpr int BM = 64 * TM;
-    static constexpr int BN = 64 * TN;
-    static constexpr int A_VECS = BM / 32;   // 16-byte vectors per thread per slab
-    static constexpr int W_VECS = BN / 32;
-};
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
 
-template <typename OT> __device__ __forceinline__ void store4(OT* p, const f32x4& v);
-template <> __device__ __forceinline__ void store4<float>(float* p, const f32x4& v) { *reinterpret_cast<f32x4*>(p) = v; }
-template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const f32x4& v) {
-    bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-    *reinterpret_cast<bf16x4*>(p) = o;
+__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
+
+__device__ __forceinline__ void load_lds16(const void* g, void* l) {
+    __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
 }
 
-template <int TM, int TN, typename OT, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
-    using T = Tile<TM, TN>;
-    __shared__ __attribute__((aligned(16))) bf16_t As[T::BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t Ws[T::BN * LDS_STRIDE];
+template <typename OT, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
 
     int tile = blockIdx.x;
     const int pi = tile >= tiles0 ? 1 : 0;
     if (pi) tile -= tiles0;
     const GemmProblem& p = g.p[pi];
-    const int row0 = (tile / tiles_n) * T::BM;
-    const int col0 = (tile % tiles_n) * T::BN;
+    const int row0 = (tile / tiles_n) * BM;
+    const int col0 = (tile % tiles_n) * BN;
     const int m = p.m, n = g.n, k = g.k;
     const bf16_t* A = static_cast<const bf16_t*>(p.a);
     const bf16_t* W = static_cast<const bf16_t*>(p.w);
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wt = wave % 2, wf = wave / 2;          // wave position: tokens, features
-    const int ld_row = tid / 8, ld_vec = tid % 8;    // global -> LDS copy role
+    const int lr = lane % 32, hi = lane / 32;
 
-    const bf16_t* a_src[T::A_VECS];
-    const bf16_t* w_src[T::W_VECS];
+    // This wave's 8 chunks of a slab: chunk c covers stage rows 8 c .. 8 c + 7 (rows 0..127 = A, 128..255 = W);
+    // lane i fills 16-byte slot i % 8 of row i / 8 and fetches k-vector (slot ^ swz(row)) for it.
+    const bf16_t* src[CPW];
 #pragma unroll
-    for (int i = 0; i < T::A_VECS; i++) a_src[i] = A + (size_t)min(row0 + ld_row + 32 * i, m - 1) * k + ld_vec * 8;
+    for (int c = 0; c < CPW; c++) {
+        const int r = (wave + 4 * c) * 8 + lane / 8;
+        const int kv = (lane % 8) ^ swz(r);
+        if (r < BM) src[c] = A + (size_t)min(row0 + r, m - 1) * k + kv * 8;
+        else src[c] = W + (size_t)min(col0 + r - BM, n - 1) * k + kv * 8;
+    }
+    auto issue = [&](int slab, int stage) {
 #pragma unroll
-    for (int i = 0; i < T::W_VECS; i++) w_src[i] = W + (size_t)min(col0 + ld_row + 32 * i, n - 1) * k + ld_vec * 8;
+        for (int c = 0; c < CPW; c++)
+            load_lds16(src[c] + (size_t)slab * BK, smem + stage * STAGE_BYTES + (wave + 4 * c) * 1024);
+    };
 
-    f32x16 acc[TN][TM];
+    f32x16 acc[2][2];   // [feature tile][token tile]
 #pragma unroll
-    for (int fn = 0; fn < TN; fn++)
+    for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-        for (int tm = 0; tm < TM; tm++)
+        for (int tm = 0; tm < 2; tm++)
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[fn][tm][i] = 0.f;
 
-    bf16x8 a_reg[T::A_VECS], w_reg[T::W_VECS];
-#pragma unroll
-    for (int i = 0; i < T::A_VECS; i++) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i]);
-#pragma unroll
-    for (int i = 0; i < T::W_VECS; i++) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i]);
-
-    const int frag_off = (lane % 32) * LDS_STRIDE + (lane / 32) * 8;
     const int nslab = k / BK;
+    issue(0, 0);
     for (int s = 0; s < nslab; s++) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of slab s has landed
+        __builtin_amdgcn_s_barrier();                      // ... and everyone else's; stage (s+1)%2 is free
+        if (s + 1 < nslab) issue(s + 1, (s + 1) & 1);
+        const unsigned char* sa = smem + (s & 1) * STAGE_BYTES;
+        const unsigned char* sw = sa + BM * ROWB;
+        bf16x8 af[2][2], wfr[2][2];   // [kk parity][tile]
+        auto read_frags = [&](int kk, bf16x8* a2, bf16x8* w2) {
 #pragma unroll
-        for (int i = 0; i < T::A_VECS; i++) *reinterpret_cast<bf16x8*>(&As[(ld_row + 32 * i) * LDS_STRIDE + ld_vec * 8]) = a_reg[i];
-#pragma unroll
-        for (int i = 0; i < T::W_VECS; i++) *reinterpret_cast<bf16x8*>(&Ws[(ld_row + 32 * i) * LDS_STRIDE + ld_vec * 8]) = w_reg[i];
-        __syncthreads();
-        if (s + 1 < nslab) {
-#pragma unroll
-            for (int i = 0; i < T::A_VECS; i++) a_reg[i] = *reinterpret_cast<const bf16x8*>(a_src[i] + (size_t)(s + 1) * BK);
-#pragma unroll
-            for (int i = 0; i < T::W_VECS; i++) w_reg[i] = *reinterpret_cast<const bf16x8*>(w_src[i] + (size_t)(s + 1) * BK);
-        }
+            for (int t = 0; t < 2; t++) {
+                const int ra = wt * 64 + t * 32 + lr, rw = wf * 64 + t * 32 + lr;
+                a2[t] = *reinterpret_cast<const bf16x8*>(sa + ra * ROWB + (((kk * 2 + hi) ^ swz(ra)) * 16));
+                w2[t] = *reinterpret_cast<const bf16x8*>(sw + rw * ROWB + (((kk * 2 + hi) ^ swz(rw + BM)) * 16));
+            }
+        };
+        read_frags(0, af[0], wfr[0]);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
-            bf16x8 af[TM], wfr[TN];
+            if (kk + 1 < BK / 16) read_frags(kk + 1, af[(kk + 1) & 1], wfr[(kk + 1) & 1]);
 #pragma unroll
-            for (int tm = 0; tm < TM; tm++)
-                af[tm] = *reinterpret_cast<const bf16x8*>(&As[(wt * 32 * TM + tm * 32) * LDS_STRIDE + frag_off + kk * 16]);
+            for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-            for (int fn = 0; fn < TN; fn++)
-                wfr[fn] = *reinterpret_cast<const bf16x8*>(&Ws[(wf * 32 * TN + fn * 32) * LDS_STRIDE + frag_off + kk * 16]);
-#pragma unroll
-            for (int fn = 0; fn < TN; fn++)
-#pragma unroll
-                for (int tm = 0; tm < TM; tm++)
-                    acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[fn], af[tm], acc[fn][tm], 0, 0, 0);
+                for (int tm = 0; tm < 2; tm++)
+                    acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[kk & 1][fn], af[kk & 1][tm], acc[fn][tm], 0, 0, 0);
         }
-        __syncthreads();
+        __builtin_amdgcn_s_barrier();                      // everyone is done reading stage s%2
     }
 
-    // Epilogue.  Register i of tile (fn, tm): feature = f_base + 8 (i / 4) + 4 (lane / 32) + i % 4,
-    // token = r_base + lane % 32.
+    // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
+    // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*64 + tm*32 + lr.
+    constexpr bool F32OUT = sizeof(OT) == 4;
+    constexpr int NPASS = F32OUT ? 2 : 1;            // an fp32 tile is staged in two 64-token halves
+    constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
+    constexpr int ROWS_PER_PASS = BM / NPASS;
+    constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
+    constexpr int CHUNKS_PER_ROW = BN / CHUNK_ELEMS;
 #pragma unroll
-    for (int tm = 0; tm < TM; tm++) {
-        const int r = row0 + wt * 32 * TM + tm * 32 + lane % 32;
-        if (r >= m) continue;
-        size_t qkv_row = 0;
-        int qb = 0;
-        if constexpr (EPI == EPI_QKV) {
-            qb = r / p.tokens;
-            qkv_row = (size_t)p.tok_offset + (r - qb * p.tokens);
-        }
-        const float* gate_row = nullptr;
-        if constexpr (EPI == EPI_GATE_RES) {
-            if (p.gate) gate_row = p.gate + (size_t)(r / p.rows_per_gate) * p.gate_stride;
-        }
+    for (int pass = 0; pass < NPASS; pass++) {
+        if (NPASS == 1 || wt == pass) {
 #pragma unroll
-        for (int fn = 0; fn < TN; fn++) {
+            for (int tm = 0; tm < 2; tm++) {
+                const int trow = (NPASS == 1 ? wt * 64 : 0) + tm * 32 + lr;      // row inside the staging tile
+                const int r = row0 + wt * 64 + tm * 32 + lr;                     // global token row
+                const float* gate_row = nullptr;
+                if constexpr (EPI == EPI_GATE_RES) {
+                    if (p.gate) gate_row = p.gate + (size_t)(min(r, m - 1) / p.rows_per_gate) * p.gate_stride;
+                }
 #pragma unroll
-            for (int gi = 0; gi < 4; gi++) {
-                const int f = col0 + wf * 32 * TN + fn * 32 + 8 * gi + 4 * (lane / 32);
-                if (f >= n) continue;
-                f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
-                if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + f);
-                if constexpr (EPI == EPI_QKV) {
-                    const int hd = p.heads * 64;
-                    const int which = f / hd, cc = f - which * hd, head = cc / 64, i0 = cc % 64;
-                    OT* base = static_cast<OT*>(which == 0 ? p.q : (which == 1 ? p.k : p.v));
-                    store4<OT>(base + (((size_t)qb * p.heads + head) * p.n_total + qkv_row) * 64 + i0, v);
-                } else {
-                    const size_t o = (size_t)r * n + f;
-                    if constexpr (EPI == EPI_GELU_TANH) {
+                for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-                        for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
-                    } else if constexpr (EPI == EPI_SILU) {
+                    for (int gi = 0; gi < 4; gi++) {
+                        const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;      // feature inside the tile
+                        const int f = min(col0 + fl, n - 4);                     // clamped: masked on store
+                        f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
+                        if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + f);
+                        if constexpr (EPI == EPI_GELU_TANH) {
 #pragma unroll
-                        for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
-                    } else if constexpr (EPI == EPI_GATE_RES) {
-                        const f32x4 res = *reinterpret_cast<const f32x4*>(p.res + o);
-                        if (gate_row) {
-                            const f32x4 gt = *reinterpret_cast<const f32x4*>(gate_row + f);
+                            for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
+                        } else if constexpr (EPI == EPI_SILU) {
 #pragma unroll
-                            for (int j = 0; j < 4; j++) v[j] = fmaf(gt[j], v[j], res[j]);
+                            for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
+                        } else if constexpr (EPI == EPI_GATE_RES) {
+                            if (gate_row) v *= *reinterpret_cast<const f32x4*>(gate_row + f);
+                        }
+                        unsigned char* dst = smem + trow * STRIDE + fl * (int)sizeof(OT);
+                        if constexpr (F32OUT) {
+                            *reinterpret_cast<f32x4*>(dst) = v;
                         } else {
-                            v += res;
+                            bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                            *reinterpret_cast<bf16x4*>(dst) = o;
                         }
                     }
-                    store4<OT>(static_cast<OT*>(p.out) + o, v);
-                }
             }
         }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = tid; c < ROWS_PER_PASS * CHUNKS_PER_ROW; c += 256) {
+            const int trow = c / CHUNKS_PER_ROW, ch = c % CHUNKS_PER_ROW;
+            const int r = row0 + pass * ROWS_PER_PASS + trow;
+            const int f = col0 + ch * CHUNK_ELEMS;
+            if (r >= m || f >= n) continue;
+            const unsigned char* srcp = smem + trow * STRIDE + ch * 16;
+            if constexpr (EPI == EPI_QKV) {
+                // feature f = (which, head, i); token row r = (sample b, token t): 8 features stay inside one head
+                const int hd = p.heads * 64;
+                const int which = f / hd, cc = f - which * hd, head = cc / 64, i0 = cc % 64;
+                const int b = r / p.tokens, t = r - b * p.tokens;
+                OT* base = static_cast<OT*>(which == 0 ? p.q : (which == 1 ? p.k : p.v));
+                OT* dst = base + (((size_t)b * p.heads + head) * p.n_total + p.tok_offset + t) * 64 + i0;
+                *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
+            } else if constexpr (EPI == EPI_GATE_RES) {
+                const size_t o = (size_t)r * n + f;
+                const f32x4 v = *reinterpret_cast<const f32x4*>(srcp) + *reinterpret_cast<const f32x4*>(p.res + o);
+                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = v;
+            } else {
+                OT* dst = static_cast<OT*>(p.out) + (size_t)r * n + f;
+                *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
+            }
+        }
+        if (pass + 1 < NPASS) __syncthreads();
     }
 }
 
-template <int TM, int TN, typename OT, int EPI>
-int launch_tile(const GemmGroup& g, hipStream_t st) {
-    using T = Tile<TM, TN>;
-    const int tiles_n = (g.n + T::BN - 1) / T::BN;
-    const int tiles0 = ((g.p[0].m + T::BM - 1) / T::BM) * tiles_n;
-    const int tiles1 = g.count > 1 ? ((g.p[1].m + T::BM - 1) / T::BM) * tiles_n : 0;
+template <typename OT, int EPI>
+int launch_epi(const GemmGroup& g, hipStream_t st) {
+    const int tiles_n = (g.n + BN - 1) / BN;
+    const int tiles0 = ((g.p[0].m + BM - 1) / BM) * tiles_n;
+    const int tiles1 = g.count > 1 ? ((g.p[1].m + BM - 1) / BM) * tiles_n : 0;
     if (tiles0 + tiles1 == 0) return HYB_OK;
     char name[96];
-    snprintf(name, sizeof(name), "gemm_mfma_%dx%d.epi%d.n%d.k%d", T::BM, T::BN, EPI, g.n, g.k);
+    snprintf(name, sizeof(name), "gemm_mfma_%dx%d.epi%d.n%d.k%d", BM, BN, EPI, g.n, g.k);
     double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
     HybTraceScope trace(name, "flop", 2.0 * rows * g.n * g.k, st);
     GemmGroup gg = g;
     if (tiles0 == 0) {  // keep problem 0 non-empty so that the tile -> problem split stays simple
         gg.p[0] = g.p[1];
         gg.count = 1;
-        hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, OT, EPI>), dim3(tiles1), dim3(256), 0, st, gg, tiles_n, tiles1);
+        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI>), dim3(tiles1), dim3(256), 0, st, gg, tiles_n, tiles1);
     } else {
-        hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, OT, EPI>), dim3(tiles0 + tiles1), dim3(256), 0, st, gg, tiles_n, tiles0);
+        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI>), dim3(tiles0 + tiles1), dim3(256), 0, st, gg, tiles_n, tiles0);
     }
     return hyb_check_launch("gemm_mfma");
-}
-
-template <typename OT, int EPI>
-int launch_epi(const GemmGroup& g, hipStream_t st) {
-    return launch_tile<2, 2, OT, EPI>(g, st);
 }
 
 }  // namespace
 
 int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st) {
-    if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || epi == EPI_GEGLU) return -1;
+    if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || g.n < 8 || epi == EPI_GEGLU) return -1;
     for (int i = 0; i < g.count; i++) {
         const GemmProblem& p = g.p[i];
         if (epi == EPI_GATE_RES && p.gate && (p.gate_stride % 4 != 0)) return -1;
