@@ -2,7 +2,9 @@
 // o = softmax(q k^T * scale) v with a streaming (online) softmax, never materialising scores.
 //
 // A workgroup of 4 waves owns 128 query rows of one (batch, head); each wave owns 32 of them.
-// Keys / values are streamed 64 at a time through double-buffered LDS tiles shared by the waves.
+// Keys / values are streamed 64 at a time through double-buffered LDS tiles shared by the waves,
+// copied global -> LDS by 16-byte direct-to-LDS loads (no VGPR staging); rows are 128 bytes,
+// unpadded, with their 16-byte slots XOR-swizzled by (row ^ row >> 3) & 7 against bank conflicts.
 // Both contractions run on v_mfma_f32_32x32x16_bf16 in TRANSPOSED form:
 //   S^T = K Q^T   (A operand: a K row per lane from LDS; B operand: the lane's query row, kept in
 //                  registers for the whole kernel)
@@ -13,8 +15,14 @@
 // contraction index inside an MFMA does not matter as long as both operands agree -- the
 // exponentiated S^T registers, rounded to bf16, ARE the B operand of the second contraction:
 // registers 8h..8h+7 of a lane hold keys {16h + 4g + 0..3, 16h + 8 + 4g + 0..3} (g = lane / 32),
-// and the matching V^T fragment is two 8-byte LDS reads at those key offsets.  V is transposed
-// on its way into LDS.  Softmax runs in fp32 with exp2 and the scale folded into one FMA.
+// and the matching V^T fragment comes from two transposing LDS reads (ds_read_b64_tr_b16) of the V
+// tile kept in its natural [key][feature] layout: in a group of 16 lanes, lane s points at 4
+// features of key (s / 4) and lane i receives feature (i) of 4 consecutive keys.
+// Softmax runs in fp32 with exp2 and the scale folded into one FMA.  The running maximum is only
+// advanced (and the output accumulator rescaled) when some row's maximum grew by more than 2^8;
+// until then exponentials are taken against the older maximum (values up to 2^8, exact same
+// result after the final normalisation up to rounding).  The normaliser is the sum of the
+// bf16-rounded probabilities that enter the second contraction (v_dot2 with ones).
 // Tail keys are masked to -inf before the row maximum; tail query rows are clamped on load
 // and not stored.  The reduction order is fixed: results are deterministic and batch-invariant.
 #include "attention.h"
@@ -23,12 +31,20 @@ namespace {
 
 constexpr int BQ = 128;
 constexpr int BKV = 64;
-constexpr int K_STRIDE = 72;   // bf16 per K row in LDS (64 + 8 pad: conflict-free 16-byte reads)
-constexpr int V_STRIDE = 68;   // bf16 per V^T row in LDS (64 keys + 4 pad: conflict-free 8-byte reads)
+constexpr int ROWB = 128;                   // bytes per K / V row in LDS
+constexpr int TILE_BYTES = BKV * ROWB;      // 8 KB per operand tile
+constexpr float RESCALE_LOG2 = 8.0f;
 
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) bf16_t Ks[2][BKV * K_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[2][64 * V_STRIDE];
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef bf16x4 __attribute__((address_space(3)))* lds_bf16x4_ptr;
+typedef const void __attribute__((address_space(1)))* gptr_t;
+typedef void __attribute__((address_space(3)))* lptr_t;
+
+__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
+
+__global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
+    // [buffer][K tile | V tile]
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * TILE_BYTES];
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int lq = lane % 32, g = lane / 32;
@@ -43,23 +59,18 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
     for (int kk = 0; kk < 4; kk++) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
 
-    const int ld_row = tid / 8, ld_vec = tid % 8;
-    bf16x8 k_reg[2], v_reg[2];
-    auto load_tile = [&](int t) {
+    // Tile copy: 16 chunks of 1 KB (8 rows) per tile pair, 4 per wave: chunks w, w+4 of K and of V.
+    // Lane i fills slot i % 8 of row i / 8 of its chunk with feature vector (slot ^ swz(row)).
+    const int cp_row = lane / 8;
+    auto issue = [&](int t, int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; i++) {
-            const size_t row = (size_t)min(t * BKV + ld_row + 32 * i, a.n_kv - 1);
-            k_reg[i] = *reinterpret_cast<const bf16x8*>(kp + row * 64 + ld_vec * 8);
-            v_reg[i] = *reinterpret_cast<const bf16x8*>(vp + row * 64 + ld_vec * 8);
-        }
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; i++) {
-            const int row = ld_row + 32 * i;
-            *reinterpret_cast<bf16x8*>(&Ks[buf][row * K_STRIDE + ld_vec * 8]) = k_reg[i];
-#pragma unroll
-            for (int j = 0; j < 8; j++) Vt[buf][(ld_vec * 8 + j) * V_STRIDE + row] = v_reg[i][j];
+        for (int c = 0; c < 2; c++) {
+            const int r = (wave + 4 * c) * 8 + cp_row;                       // row inside the tile
+            const size_t grow = (size_t)min(t * BKV + r, a.n_kv - 1);        // clamped; masked in the scores
+            const int fv = (lane % 8) ^ swz(r);
+            unsigned char* dst = smem[buf] + (wave + 4 * c) * 1024;
+            __builtin_amdgcn_global_load_lds((gptr_t)(kp + grow * 64 + fv * 8), (lptr_t)dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(vp + grow * 64 + fv * 8), (lptr_t)(dst + TILE_BYTES), 16, 0, 0);
         }
     };
 
@@ -71,22 +82,32 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; i++) o[dt][i] = 0.f;
 
+    // V^T fragments by transposing reads: lane (group G = lane / 16, s = lane % 16) points at features
+    // dt*32 + 16 (G % 2) + 4 (s % 4) .. +3 of key k0 + s / 4 and receives feature dt*32 + lane % 32 of
+    // keys k0 .. k0 + 3 (k0 = kt*32 + hf*16 + 4 g; second read: + 8).
+    const int sl = lane % 16;
+    const int v_key = 4 * g + sl / 4;                                  // + kt*32 + hf*16 (+8)
+    const int v_feat = 16 * ((lane / 16) % 2) + 4 * (sl % 4);          // + dt*32
+
     const int nt = (a.n_kv + BKV - 1) / BKV;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    issue(0, 0);
     for (int t = 0; t < nt; t++) {
         const int cur = t & 1;
-        if (t + 1 < nt) load_tile(t + 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile t has landed
+        __builtin_amdgcn_s_barrier();                      // ... everyone's; and buffer cur^1 is free again
+        if (t + 1 < nt) issue(t + 1, cur ^ 1);
+        const unsigned char* ks = smem[cur];
+        const unsigned char* vs = ks + TILE_BYTES;
 
         f32x16 s[2];
 #pragma unroll
         for (int kt = 0; kt < 2; kt++) {
 #pragma unroll
             for (int i = 0; i < 16; i++) s[kt][i] = 0.f;
+            const int r = kt * 32 + lq;
 #pragma unroll
             for (int kk = 0; kk < 4; kk++) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[cur][(kt * 32 + lq) * K_STRIDE + kk * 16 + g * 8]);
+                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + r * ROWB + (((kk * 2 + g) ^ swz(r)) * 16));
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[kt], 0, 0, 0);
             }
         }
@@ -99,31 +120,40 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
                     if (key >= a.n_kv) s[kt][i] = -__builtin_inff();
                 }
         }
-        float mx = s[0][0];
+        float mx = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++)
+        for (int i = 1; i < 16; i += 3) mx = fmaxf(fmaxf(mx, s[0][i]), fmaxf(s[0][i + 1], s[0][i + 2]));
 #pragma unroll
-            for (int i = 0; i < 16; i++) mx = fmaxf(mx, s[kt][i]);
+        for (int i = 1; i < 16; i += 3) mx = fmaxf(fmaxf(mx, s[1][i]), fmaxf(s[1][i + 1], s[1][i + 2]));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);
-        const float mc = m_new * c;
-        m_run = m_new;
-        float psum = 0.f;
+        // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
+        const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
+        if (__any(grow)) {
+            const float m_new = grow ? mx : m_run;
+            const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);   // 1 where unchanged, 0 on the first tile
+            m_run = m_new;
+            l_run *= corr;
+#pragma unroll
+            for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) o[dt][i] *= corr;
+        }
+        const float mc = m_run * c;
         bf16x8 pb[2][2];
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
-                psum += p;
-                pb[kt][i / 8][i % 8] = (bf16_t)p;
-            }
-        l_run = fmaf(l_run, corr, psum);
+            for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
+        const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 #pragma unroll
-        for (int dt = 0; dt < 2; dt++)
+        for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) o[dt][i] *= corr;
+            for (int hf = 0; hf < 2; hf++)
+#pragma unroll
+                for (int j = 0; j < 8; j += 2) {
+                    const bf16x2 pr = {pb[kt][hf][j], pb[kt][hf][j + 1]};
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
+                }
 
 #pragma unroll
         for (int dt = 0; dt < 2; dt++)
@@ -131,15 +161,14 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnArgs a) {
             for (int kt = 0; kt < 2; kt++)
 #pragma unroll
                 for (int hf = 0; hf < 2; hf++) {
-                    const bf16_t* vrow = &Vt[cur][(dt * 32 + lq) * V_STRIDE + kt * 32 + hf * 16 + 4 * g];
-                    const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vrow);
-                    const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vrow + 8);
+                    const int key = kt * 32 + hf * 16 + v_key, feat = dt * 32 + v_feat;
+                    const unsigned char* p0 = vs + key * ROWB + (((feat / 8) ^ swz(key)) * 16) + (feat % 8) * 2;
+                    const unsigned char* p1 = vs + (key + 8) * ROWB + (((feat / 8) ^ swz(key + 8)) * 16) + (feat % 8) * 2;
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p0);
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p1);
                     const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kt][hf], o[dt], 0, 0, 0);
                 }
-
-        if (t + 1 < nt) store_tile(cur ^ 1);
-        __syncthreads();
     }
 
     if (qrow >= a.n_q) return;
