@@ -199,6 +199,64 @@ int hyb_unpatchify(const void* tokens, void* latent, int batch, int hh, int ww, 
 int hyb_convert(const float* in, void* out, size_t n, hyb_dtype out_dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Second denoiser shape (the U-Net family of Sec. 5's setup): one transformer block of an
+ * SDXL-shaped attention stage on token-major activations.
+ * ---------------------------------------------------------------------------------------- */
+
+/* out = GroupNorm(x) * gamma + beta on x[batch, tokens, channels]: groups of channels / groups
+ * consecutive channels, statistics over (tokens, channels / groups) per sample, biased variance.
+ * x, out: device float (may alias); gamma, beta: device float[channels]; workspace: device,
+ * >= hyb_groupnorm_workspace_bytes(batch, groups).  channels % (4 * groups) == 0, channels <= 4096. */
+int hyb_groupnorm(const float* x, const float* gamma, const float* beta, float* out,
+                  int batch, int tokens, int channels, int groups, float eps,
+                  void* workspace, size_t workspace_bytes, void* stream);
+size_t hyb_groupnorm_workspace_bytes(int batch, int groups);
+
+/* out[r, :] = LN(x[r, :]) * gamma + beta (biased variance).  x: device float[rows, hidden];
+ * gamma, beta: device float[hidden]; out: device [rows, hidden] of `out_dtype`.  hidden % 4 == 0, <= 2048. */
+int hyb_layernorm_affine(const float* x, const float* gamma, const float* beta, void* out,
+                         int rows, int hidden, float eps, hyb_dtype out_dtype, void* stream);
+
+typedef struct {
+    int batch;        /* samples (2 = conditional + unconditional) */
+    int tokens;       /* spatial tokens per sample */
+    int channels;     /* C = heads * head_dim */
+    int heads;
+    int head_dim;     /* must be 64 */
+    int n_ctx;        /* text tokens per sample */
+    int ctx_dim;      /* text feature width (multiple of 64 for bf16) */
+    int groups;       /* GroupNorm groups (32) */
+    hyb_dtype dtype;
+    float gn_eps;     /* 1e-5 */
+    float ln_eps;     /* 1e-5 */
+} hyb_sdxl_block_desc;
+
+typedef struct {
+    const float *gn_g, *gn_b, *ln1_g, *ln1_b, *ln2_g, *ln2_b, *ln3_g, *ln3_b;   /* fp32 [C] */
+    const void* w_qkv1;   /* [3C, C]: rows = [Wq; Wk; Wv] of the self-attention (no bias) */
+    const void* w_o1;     /* [C, C] */
+    const float* b_o1;
+    const void* w_q2;     /* [C, C] (no bias) */
+    const void* w_kv2;    /* [2C, ctx_dim]: rows = [Wk; Wv] of the cross-attention (no bias) */
+    const void* w_o2;     /* [C, C] */
+    const float* b_o2;
+    const void* w_ff1;    /* [8C, C]: rows [0, 4C) = value half, rows [4C, 8C) = gate half */
+    const float* b_ff1;   /* [8C] */
+    const void* w_ff2;    /* [C, 4C] */
+    const float* b_ff2;
+} hyb_sdxl_block_weights;
+
+/* g = GroupNorm(x); a = g + SelfAttn(LN(g)); b = a + CrossAttn(LN(a), ctx);
+ * out = x + b + W2 (u * GELUerf(gate)) + b2 with [u, gate] = LN(b) W1^T + b1 (heads of 64 features,
+ * attention scale 1/8, LayerNorms with gamma / beta).
+ * x_in, x_out: device float[batch, tokens, channels] (may alias); ctx: device [batch, n_ctx, ctx_dim]
+ * of desc->dtype; workspace: device, >= hyb_sdxl_block_workspace_bytes(desc). */
+int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb_sdxl_block_weights* weights,
+                           const float* x_in, const void* ctx, float* x_out,
+                           void* workspace, size_t workspace_bytes, void* stream);
+size_t hyb_sdxl_block_workspace_bytes(const hyb_sdxl_block_desc* desc);
+
+/* ------------------------------------------------------------------------------------------
  * Optional per-launch timing, for benchmarks (callers that measure, not the paper's method).
  * While enabled, every kernel launch of the library is bracketed by two events on its stream.
  * hyb_trace_enable(1) clears earlier records.  hyb_trace_summary waits for the recorded events

@@ -37,6 +37,20 @@ class BlockWeights(C.Structure):
     _fields_ = [("img", StreamWeights), ("txt", StreamWeights)]
 
 
+class SdxlBlockDesc(C.Structure):
+    _fields_ = [("batch", C.c_int), ("tokens", C.c_int), ("channels", C.c_int), ("heads", C.c_int),
+                ("head_dim", C.c_int), ("n_ctx", C.c_int), ("ctx_dim", C.c_int), ("groups", C.c_int),
+                ("dtype", C.c_int), ("gn_eps", C.c_float), ("ln_eps", C.c_float)]
+
+
+SDXL_WEIGHT_FIELDS = ("gn_g", "gn_b", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "ln3_g", "ln3_b", "w_qkv1", "w_o1", "b_o1",
+                      "w_q2", "w_kv2", "w_o2", "b_o2", "w_ff1", "b_ff1", "w_ff2", "b_ff2")
+
+
+class SdxlBlockWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in SDXL_WEIGHT_FIELDS]
+
+
 _vp, _i, _f, _sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
 SIGNATURES = {
     "hyb_version": (C.c_int, []),
@@ -58,6 +72,11 @@ SIGNATURES = {
     "hyb_patchify": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _vp]),
     "hyb_unpatchify": (_i, [_vp, _vp, _i, _i, _i, _i, _i, _i, _i, _vp]),
     "hyb_convert": (_i, [_vp, _vp, _sz, _i, _vp]),
+    "hyb_groupnorm": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _vp, _sz, _vp]),
+    "hyb_groupnorm_workspace_bytes": (_sz, [_i, _i]),
+    "hyb_layernorm_affine": (_i, [_vp, _vp, _vp, _vp, _i, _i, _f, _i, _vp]),
+    "hyb_sdxl_block_forward": (_i, [C.POINTER(SdxlBlockDesc), C.POINTER(SdxlBlockWeights), _vp, _vp, _vp, _vp, _sz, _vp]),
+    "hyb_sdxl_block_workspace_bytes": (_sz, [C.POINTER(SdxlBlockDesc)]),
     "hyb_trace_enable": (_i, [_i]),
     "hyb_trace_summary": (_i, [C.c_char_p, _sz]),
 }
@@ -259,3 +278,42 @@ def hyb_trace_summary():
         name, unit, count, ms, work = line.split("\t")
         out[name] = {"unit": unit, "launches": int(count), "ms": float(ms), "work": float(work)}
     return out
+
+
+def hyb_groupnorm_workspace_bytes(batch, groups):
+    return lib().hyb_groupnorm_workspace_bytes(batch, groups)
+
+
+def hyb_groupnorm(x, gamma, beta, out, groups, eps, workspace):
+    """x, out: f32[B, T, C]."""
+    B, T, Cc = x.shape
+    _check(lib().hyb_groupnorm(_p(x, torch.float32), _p(gamma, torch.float32), _p(beta, torch.float32),
+                               _p(out, torch.float32), B, T, Cc, groups, eps, _p(workspace), _nbytes(workspace), _stream()))
+    return out
+
+
+def hyb_layernorm_affine(x, gamma, beta, out, eps):
+    """x: f32[..., hidden]; out: same shape."""
+    hidden = x.shape[-1]
+    _check(lib().hyb_layernorm_affine(_p(x, torch.float32), _p(gamma, torch.float32), _p(beta, torch.float32), _p(out),
+                                      x.numel() // hidden, hidden, eps, _dt(out), _stream()))
+    return out
+
+
+def sdxl_block_desc(batch, tokens, channels, heads, n_ctx, ctx_dim, dtype, groups=32, gn_eps=1e-5, ln_eps=1e-5):
+    return SdxlBlockDesc(batch, tokens, channels, heads, 64, n_ctx, ctx_dim, groups, dtype, gn_eps, ln_eps)
+
+
+def sdxl_block_weights(d):
+    """d: dict of device tensors named as the fields of hyb_sdxl_block_weights."""
+    return SdxlBlockWeights(*[d[n].data_ptr() for n in SDXL_WEIGHT_FIELDS])
+
+
+def hyb_sdxl_block_workspace_bytes(desc):
+    return lib().hyb_sdxl_block_workspace_bytes(C.byref(desc))
+
+
+def hyb_sdxl_block_forward(desc, weights, x_in, ctx, x_out, workspace):
+    _check(lib().hyb_sdxl_block_forward(C.byref(desc), C.byref(weights), _p(x_in, torch.float32), _p(ctx),
+                                        _p(x_out, torch.float32), _p(workspace), _nbytes(workspace), _stream()))
+    return x_out

@@ -9,8 +9,8 @@ enum GemmEpi {
     EPI_BIAS = 0,        // out[r, c] = acc + bias[c]
     EPI_GELU_TANH = 1,   // out[r, c] = GELUtanh(acc + bias[c])
     EPI_SILU = 2,        // out[r, c] = SiLU(acc + bias[c])
-    EPI_GATE_RES = 3,    // out[r, c] (fp32) = res[r, c] + gate[(r / rows_per_gate) * gate_stride + c] * (acc + bias[c])
-    EPI_QKV = 4,         // scatter (acc + bias[c]) to head-major q / k / v
+    EPI_GATE_RES = 3,    // out[r, c] (fp32) = res[r, c] (+ res2[r, c]) + gate[(r / rows_per_gate) * gate_stride + c] * (acc + bias[c])
+    EPI_QKV = 4,         // scatter (acc + bias[c]) to head-major q / k / v (n = 1, 2 or 3 times heads * 64)
     EPI_GEGLU = 5        // out[r, c] = (acc_u + bias[c]) * GELUerf(acc_g + bias[n + c]), W rows [u; g] (2n rows)
 };
 
@@ -24,6 +24,7 @@ struct GemmProblem {
     int m;
     // EPI_GATE_RES
     const float* res;
+    const float* res2;   // optional second residual
     const float* gate;   // nullptr -> 1
     int rows_per_gate;
     size_t gate_stride;
@@ -64,6 +65,7 @@ __device__ __forceinline__ void gemm_store_scalar(const GemmProblem& p, int epi,
     else if (epi == EPI_GATE_RES) {
         const float g = p.gate ? p.gate[(size_t)(r / p.rows_per_gate) * p.gate_stride + c] : 1.f;
         v = fmaf(g, v, p.res[o]);
+        if (p.res2) v += p.res2[o];
     }
     static_cast<OT*>(p.out)[o] = from_f32<OT>(v);
 }

@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     if (pi) tile -= tiles0;
     const GemmProblem& p = g.p[pi];
     const int row0 = (tile / tiles_n) * BM;
-    const int col0 = (tile % tiles_n) * BN;
+    // EPI_GEGLU: a tile covers 64 output features; its 128 weight rows are 64 "u" rows and the 64 "gate" rows n above
+    const int col0 = (tile % tiles_n) * (EPI == EPI_GEGLU ? BN / 2 : BN);
     const int m = p.m, n = g.n, k = g.k;
     const bf16_t* A = static_cast<const bf16_t*>(p.a);
     const bf16_t* W = static_cast<const bf16_t*>(p.w);
@@ -72,7 +73,10 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
         const int r = (wave + 4 * c) * 8 + lane / 8;
         const int kv = (lane % 8) ^ swz(r);
         if (r < BM) src[c] = A + (size_t)min(row0 + r, m - 1) * k + kv * 8;
-        else src[c] = W + (size_t)min(col0 + r - BM, n - 1) * k + kv * 8;
+        else if constexpr (EPI == EPI_GEGLU) {
+            const int vr = r - BM;
+            src[c] = W + (size_t)(vr < 64 ? min(col0 + vr, n - 1) : n + min(col0 + vr - 64, n - 1)) * k + kv * 8;
+        } else src[c] = W + (size_t)min(col0 + r - BM, n - 1) * k + kv * 8;
     }
     auto issue = [&](int slab, int stage) {
 #pragma unroll
@@ -120,12 +124,14 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
 
     // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
     // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*64 + tm*32 + lr.
-    constexpr bool F32OUT = sizeof(OT) == 4;
+    constexpr bool GEGLU = EPI == EPI_GEGLU;
+    constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
     constexpr int NPASS = F32OUT ? 2 : 1;            // an fp32 tile is staged in two 64-token halves
     constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
     constexpr int ROWS_PER_PASS = BM / NPASS;
     constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
-    constexpr int CHUNKS_PER_ROW = BN / CHUNK_ELEMS;
+    constexpr int CHUNKS_PER_ROW = (GEGLU ? BN / 2 : BN) / CHUNK_ELEMS;
+    constexpr int SE = F32OUT ? 4 : 2;                  // bytes per staged element
 #pragma unroll
     for (int pass = 0; pass < NPASS; pass++) {
         if (NPASS == 1 || wt == pass) {
@@ -142,7 +148,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
 #pragma unroll
                     for (int gi = 0; gi < 4; gi++) {
                         const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;      // feature inside the tile
-                        const int f = min(col0 + fl, n - 4);                     // clamped: masked on store
+                        int f = min(col0 + fl, n - 4);                           // clamped: masked on store
+                        if constexpr (GEGLU) f = fl < 64 ? min(col0 + fl, n - 4) : n + min(col0 + fl - 64, n - 4);
                         f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
                         if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + f);
                         if constexpr (EPI == EPI_GELU_TANH) {
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
                         } else if constexpr (EPI == EPI_GATE_RES) {
                             if (gate_row) v *= *reinterpret_cast<const f32x4*>(gate_row + f);
                         }
-                        unsigned char* dst = smem + trow * STRIDE + fl * (int)sizeof(OT);
+                        unsigned char* dst = smem + trow * STRIDE + fl * SE;
                         if constexpr (F32OUT) {
                             *reinterpret_cast<f32x4*>(dst) = v;
                         } else {
@@ -171,6 +178,15 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
             const int r = row0 + pass * ROWS_PER_PASS + trow;
             const int f = col0 + ch * CHUNK_ELEMS;
             if (r >= m || f >= n) continue;
+            if constexpr (GEGLU) {
+                // 8 outputs: u at staged columns 8 ch .. 8 ch + 7, gate 64 columns further
+                const float* su = reinterpret_cast<const float*>(smem + trow * STRIDE) + ch * 8;
+                bf16x8 o8;
+#pragma unroll
+                for (int j = 0; j < 8; j++) o8[j] = (bf16_t)(su[j] * gelu_erf_f(su[64 + j]));
+                *reinterpret_cast<bf16x8*>(static_cast<bf16_t*>(p.out) + (size_t)r * n + f) = o8;
+                continue;
+            }
             const unsigned char* srcp = smem + trow * STRIDE + ch * 16;
             if constexpr (EPI == EPI_QKV) {
                 // feature f = (which, head, i); token row r = (sample b, token t): 8 features stay inside one head
@@ -182,7 +198,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
             } else if constexpr (EPI == EPI_GATE_RES) {
                 const size_t o = (size_t)r * n + f;
-                const f32x4 v = *reinterpret_cast<const f32x4*>(srcp) + *reinterpret_cast<const f32x4*>(p.res + o);
+                f32x4 v = *reinterpret_cast<const f32x4*>(srcp) + *reinterpret_cast<const f32x4*>(p.res + o);
+                if (p.res2) v += *reinterpret_cast<const f32x4*>(p.res2 + o);
                 *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = v;
             } else {
                 OT* dst = static_cast<OT*>(p.out) + (size_t)r * n + f;
@@ -195,7 +212,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
 
 template <typename OT, int EPI>
 int launch_epi(const GemmGroup& g, hipStream_t st) {
-    const int tiles_n = (g.n + BN - 1) / BN;
+    const int tile_cols = EPI == EPI_GEGLU ? BN / 2 : BN;
+    const int tiles_n = (g.n + tile_cols - 1) / tile_cols;
     const int tiles0 = ((g.p[0].m + BM - 1) / BM) * tiles_n;
     const int tiles1 = g.count > 1 ? ((g.p[1].m + BM - 1) / BM) * tiles_n : 0;
     if (tiles0 + tiles1 == 0) return HYB_OK;
@@ -217,11 +235,11 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
 }  // namespace
 
 int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st) {
-    if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || g.n < 8 || epi == EPI_GEGLU) return -1;
+    if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || g.n < 8) return -1;
     for (int i = 0; i < g.count; i++) {
         const GemmProblem& p = g.p[i];
         if (epi == EPI_GATE_RES && p.gate && (p.gate_stride % 4 != 0)) return -1;
-        if (epi == EPI_QKV && g.n != 3 * p.heads * 64) return -1;
+        if (epi == EPI_QKV && (p.heads <= 0 || g.n % (p.heads * 64) != 0 || g.n / (p.heads * 64) > 3)) return -1;
     }
     const bool f32 = out_dtype == HYB_F32;
     switch (epi) {
@@ -230,6 +248,7 @@ int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipSt
         case EPI_SILU: return f32 ? launch_epi<float, EPI_SILU>(g, st) : launch_epi<bf16_t, EPI_SILU>(g, st);
         case EPI_GATE_RES: return f32 ? launch_epi<float, EPI_GATE_RES>(g, st) : -1;
         case EPI_QKV: return f32 ? -1 : launch_epi<bf16_t, EPI_QKV>(g, st);
+        case EPI_GEGLU: return f32 ? -1 : launch_epi<bf16_t, EPI_GEGLU>(g, st);
         default: return -1;
     }
 }

@@ -137,43 +137,73 @@ __global__ __launch_bounds__(256) void adaln_kernel(const WT* __restrict__ w, co
 }
 
 // ------------------------------------------------------------------------------------------
-// GroupNorm on token-major data x[B, T, C]: one workgroup per (sample, group) computes the
-// statistics over (T, C/G) in two passes (fp32 per thread, fp64 across threads), then normalises.
+// GroupNorm on token-major data x[B, T, C], groups of C/G consecutive channels, statistics over
+// (T, C/G) per sample.  Two kernels, both with one thread per 4-channel vector (so every load and
+// store is a coalesced 16-byte access and a thread stays inside one group):
+//  1. each workgroup sums x and x^2 over its chunk of tokens (fp32 per thread, then the threads of a
+//     group are added in a fixed order in fp64) -> partial[b][chunk][group][2];
+//  2. each workgroup adds the partials of a sample in chunk order (fp64), forms mean and 1/std, and
+//     normalises its chunk: y = (x - mean) rstd gamma + beta.
+// No atomics: the result is deterministic and independent of the batch index.
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void groupnorm_kernel(const float* __restrict__ x, const float* __restrict__ gamma,
-                                                        const float* __restrict__ beta, float* __restrict__ out,
-                                                        int tokens, int channels, int groups, float eps) {
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int cg = channels / groups;
-    const float* xb = x + (size_t)b * tokens * channels + g * cg;
-    float* ob = out + (size_t)b * tokens * channels + g * cg;
-    const int n = tokens * cg;
-    __shared__ double red[4];
-    __shared__ float stat[2];
-    const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
-    float s = 0.f;
-    for (int i = threadIdx.x; i < n; i += 256) s += xb[(size_t)(i / cg) * channels + i % cg];
-    double ws = wave_sum((double)s);
-    if (lane == 0) red[wave] = ws;
-    __syncthreads();
-    if (threadIdx.x == 0) stat[0] = (float)(((red[0] + red[1]) + (red[2] + red[3])) / n);
-    __syncthreads();
-    const float mean = stat[0];
-    float q = 0.f;
-    for (int i = threadIdx.x; i < n; i += 256) {
-        const float d = xb[(size_t)(i / cg) * channels + i % cg] - mean;
-        q = fmaf(d, d, q);
+constexpr int kGnChunks = 128;
+
+__global__ void groupnorm_stats_kernel(const float* __restrict__ x, double* __restrict__ partial, int tokens,
+                                       int channels, int groups, int tokens_per_chunk) {
+    extern __shared__ float gn_red[];   // [nvec][2]
+    const int nvec = channels / 4, vec = threadIdx.x;
+    const int chunk = blockIdx.x, b = blockIdx.y;
+    const int t0 = chunk * tokens_per_chunk, t1 = min(tokens, t0 + tokens_per_chunk);
+    const f32x4* xb = reinterpret_cast<const f32x4*>(x + (size_t)b * tokens * channels);
+    float s = 0.f, q = 0.f;
+    for (int t = t0; t < t1; t++) {
+        const f32x4 v = xb[(size_t)t * nvec + vec];
+        s += (v[0] + v[1]) + (v[2] + v[3]);
+        q = fmaf(v[0], v[0], q); q = fmaf(v[1], v[1], q); q = fmaf(v[2], v[2], q); q = fmaf(v[3], v[3], q);
     }
-    ws = wave_sum((double)q);
-    if (lane == 0) red[wave] = ws;
+    gn_red[2 * vec] = s;
+    gn_red[2 * vec + 1] = q;
     __syncthreads();
-    if (threadIdx.x == 0) stat[1] = (float)(1.0 / sqrt(((red[0] + red[1]) + (red[2] + red[3])) / n + (double)eps));
-    __syncthreads();
-    const float rstd = stat[1];
-    for (int i = threadIdx.x; i < n; i += 256) {
-        const int c = i % cg;
-        const size_t o = (size_t)(i / cg) * channels + c;
-        ob[o] = fmaf((xb[o] - mean) * rstd, gamma[g * cg + c], beta[g * cg + c]);
+    if (vec < groups) {
+        const int vpg = nvec / groups;
+        double ds = 0.0, dq = 0.0;
+        for (int i = 0; i < vpg; i++) {
+            ds += (double)gn_red[2 * (vec * vpg + i)];
+            dq += (double)gn_red[2 * (vec * vpg + i) + 1];
+        }
+        double* o = partial + (((size_t)b * gridDim.x + chunk) * groups + vec) * 2;
+        o[0] = ds;
+        o[1] = dq;
+    }
+}
+
+__global__ void groupnorm_apply_kernel(const float* __restrict__ x, const double* __restrict__ partial,
+                                       const float* __restrict__ gamma, const float* __restrict__ beta,
+                                       float* __restrict__ out, int tokens, int channels, int groups,
+                                       int tokens_per_chunk, float eps) {
+    const int nvec = channels / 4, vec = threadIdx.x;
+    const int chunk = blockIdx.x, b = blockIdx.y, nchunks = gridDim.x;
+    const int grp = vec / (nvec / groups);
+    double ds = 0.0, dq = 0.0;
+    for (int c = 0; c < nchunks; c++) {
+        const double* p = partial + (((size_t)b * nchunks + c) * groups + grp) * 2;
+        ds += p[0];
+        dq += p[1];
+    }
+    const double cnt = (double)tokens * (channels / groups);
+    const double mean_d = ds / cnt;
+    const double var_d = fmax(dq / cnt - mean_d * mean_d, 0.0);
+    const float mean = (float)mean_d, rstd = (float)(1.0 / sqrt(var_d + (double)eps));
+    const f32x4 gm = reinterpret_cast<const f32x4*>(gamma)[vec], bt = reinterpret_cast<const f32x4*>(beta)[vec];
+    const f32x4* xb = reinterpret_cast<const f32x4*>(x + (size_t)b * tokens * channels);
+    f32x4* ob = reinterpret_cast<f32x4*>(out + (size_t)b * tokens * channels);
+    const int t0 = chunk * tokens_per_chunk, t1 = min(tokens, t0 + tokens_per_chunk);
+    for (int t = t0; t < t1; t++) {
+        const f32x4 v = xb[(size_t)t * nvec + vec];
+        f32x4 y;
+#pragma unroll
+        for (int j = 0; j < 4; j++) y[j] = fmaf((v[j] - mean) * rstd, gm[j], bt[j]);
+        ob[(size_t)t * nvec + vec] = y;
     }
 }
 
@@ -233,10 +263,24 @@ int hyb_launch_layernorm(const float* x, const float* shift, const float* scale,
     return hyb_check_launch("layernorm");
 }
 
+size_t hyb_groupnorm_scratch_bytes(int batch, int groups) {
+    return hyb_align_up((size_t)batch * kGnChunks * groups * 2 * sizeof(double), 256);
+}
+
+// channels % (4 * groups) == 0 and channels <= 4096 (one thread per 4-channel vector, <= 1024 threads).
 int hyb_launch_groupnorm(const float* x, const float* gamma, const float* beta, float* out, int batch, int tokens,
-                         int channels, int groups, float eps, hipStream_t st) {
+                         int channels, int groups, float eps, void* scratch, hipStream_t st) {
     if (batch == 0 || tokens == 0) return HYB_OK;
-    hipLaunchKernelGGL(groupnorm_kernel, dim3(groups, batch), dim3(256), 0, st, x, gamma, beta, out, tokens, channels, groups, eps);
+    HYB_REQUIRE(channels % (4 * groups) == 0 && channels <= 4096 && groups <= channels / 4, HYB_ERR_SHAPE,
+                "groupnorm: channels %d must be a multiple of 4 * groups (%d) and at most 4096", channels, groups);
+    const int nvec = channels / 4;
+    const int nchunks = tokens < kGnChunks ? tokens : kGnChunks;
+    const int tpc = (tokens + nchunks - 1) / nchunks;
+    const int used = (tokens + tpc - 1) / tpc;     // chunks that actually hold tokens
+    dim3 grid(used, batch), block(nvec);
+    HybTraceScope trace("groupnorm", "byte", (double)batch * tokens * channels * 12, st);
+    hipLaunchKernelGGL(groupnorm_stats_kernel, grid, block, nvec * 2 * sizeof(float), st, x, (double*)scratch, tokens, channels, groups, tpc);
+    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, block, 0, st, x, (const double*)scratch, gamma, beta, out, tokens, channels, groups, tpc, eps);
     return hyb_check_launch("groupnorm");
 }
 

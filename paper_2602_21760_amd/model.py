@@ -126,3 +126,34 @@ class GuidedSampler:
         hb.hyb_cfg_disc_euler(v[0:1], v[1:2], x.view(1, -1), x.view(1, -1), self.scale, t, t_next,
                               disc_l1=self.disc[0, i:i + 1], disc_l2=self.disc[1, i:i + 1], workspace=self.ws)
         return x
+
+
+class SDXLStage:
+    """Device-resident weights + workspace of one SDXL-shaped transformer stage (see synth.SDXLStageConfig).
+    The separate q / k / v (and k / v) projection matrices are concatenated once at load time."""
+
+    def __init__(self, cfg, blocks_iter):
+        self.cfg = cfg
+        self.act = _TORCH_DT[cfg.dtype]
+        self.hdt = hb.HYB_BF16 if cfg.dtype == "bf16" else hb.HYB_F32
+        self.blocks, self._keep = [], []
+        for w in blocks_iter:
+            d = {n: _dev(w[n]) for n in ("gn_g", "gn_b", "ln1_g", "ln1_b", "ln2_g", "ln2_b", "ln3_g", "ln3_b")}
+            d["w_qkv1"] = _dev(np.concatenate([w["q1_w"], w["k1_w"], w["v1_w"]]), self.act)
+            d["w_kv2"] = _dev(np.concatenate([w["k2_w"], w["v2_w"]]), self.act)
+            for dst, src in (("w_o1", "o1_w"), ("w_q2", "q2_w"), ("w_o2", "o2_w"), ("w_ff1", "ff1_w"), ("w_ff2", "ff2_w")):
+                d[dst] = _dev(w[src], self.act)
+            for dst, src in (("b_o1", "o1_b"), ("b_o2", "o2_b"), ("b_ff1", "ff1_b"), ("b_ff2", "ff2_b")):
+                d[dst] = _dev(w[src])
+            self._keep.append(d)
+            self.blocks.append(hb.sdxl_block_weights(d))
+        self.desc = hb.sdxl_block_desc(cfg.batch, cfg.tokens, cfg.channels, cfg.heads, cfg.n_ctx, cfg.ctx_dim, self.hdt)
+        self.ws = torch.empty(max(hb.hyb_sdxl_block_workspace_bytes(self.desc), 256), device="cuda", dtype=torch.uint8)
+        self.ctx_act = torch.empty(cfg.batch, cfg.n_ctx, cfg.ctx_dim, device="cuda", dtype=self.act)
+
+    def forward(self, x, ctx):
+        """x: f32[B, T, C] (updated in place); ctx: f32[B, n_ctx, ctx_dim]."""
+        hb.hyb_convert(ctx, self.ctx_act)
+        for bw in self.blocks:
+            hb.hyb_sdxl_block_forward(self.desc, bw, x, self.ctx_act, x, self.ws)
+        return x
