@@ -84,12 +84,68 @@ def guidance_roofline(hb, torch, steps):
     return out
 
 
+def timed(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def secondary_workloads(m, hb, model, synth, torch):
+    """The other workload shapes on the same kernels (reported, not the headline metric): the guided step
+    with both branches batched (configs[2]), the 2048 x 2048 branch (configs[3]) and the SDXL-shaped stages
+    (configs[4]).  Weights of the MMDiT are reused; only activation buffers change."""
+    out = {}
+    # configs[2]: batch 2 + fused guidance pass, per guided step
+    cfg3 = synth.CFG3
+    m.reconfigure(cfg3)
+    gs = model.GuidedSampler(m, cfg3.guidance)
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg3)
+    x = torch.from_numpy(lat).cuda()
+    ctx2 = torch.from_numpy(__import__("numpy").stack([ctx_c, ctx_u])).cuda()
+    ms = timed(lambda: gs.step(x, ctx2, 0.5, 0.45, 0), 5, 2, torch)
+    fl = cfg3.flops_per_sample() * 2
+    out["configs[2] guided step (batch 2 + CFG/discrepancy/Euler)"] = {"ms_per_step": round(ms, 3), "tflops": round(fl / ms / 1e9, 1),
+                                                                      "ms_for_28_steps": round(ms * 28, 1)}
+    # configs[3]: 2048 x 2048 branch
+    cfg4 = synth.CFG4
+    m.reconfigure(cfg4, pos_np=synth.normal(4, (cfg4.n_img, cfg4.hidden), 0.02, cfg4.dtype))
+    lat4, ctx4, _ = synth.mmdit_inputs(cfg4)
+    l4, c4 = torch.from_numpy(lat4[None]).cuda(), torch.from_numpy(ctx4[None]).cuda()
+    t4 = torch.full((1,), 0.5, device="cuda")
+    ms = timed(lambda: m.forward(l4, c4, t4), 3, 1, torch)
+    out["configs[3] 2048x2048 branch forward"] = {"ms_per_step": round(ms, 3), "tflops": round(cfg4.flops_per_sample() / ms / 1e9, 1)}
+    return out
+
+
+def sdxl_workload(hb, model, synth, torch):
+    out = {}
+    total_ms, total_fl = 0.0, 0.0
+    for cfg in (synth.CFG5A, synth.CFG5B):
+        st = model.SDXLStage(cfg, (synth.sdxl_block_weights(cfg, i) for i in range(cfg.blocks)))
+        x, ctx = synth.sdxl_inputs(cfg)
+        dx, dc = torch.from_numpy(x).cuda(), torch.from_numpy(ctx).cuda()
+        ms = timed(lambda: st.forward(dx, dc), 5, 2, torch)
+        fl = cfg.flops_per_sample() * cfg.batch
+        out[cfg.name] = {"ms": round(ms, 3), "tflops": round(fl / ms / 1e9, 1)}
+        total_ms += ms
+        total_fl += fl
+        del st
+    out["stages A+B, batch 2"] = {"ms": round(total_ms, 3), "tflops": round(total_fl / total_ms / 1e9, 1)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true", help="skip the other workload shapes")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the two guidance branches are batched or run "
@@ -147,13 +203,19 @@ def main():
                 "us_per_launch": d["ms"] / d["launches"] * 1e3, "flops_per_launch": d["work"] / d["launches"]}
 
     guidance = guidance_roofline(hb, torch, max(args.steps, 10))
+    secondary = {}
+    if not args.no_secondary:
+        secondary = secondary_workloads(m, hb, model, synth, torch)
+        del m
+        torch.cuda.empty_cache()
+        secondary["configs[4] SDXL-shaped stages"] = sdxl_workload(hb, model, synth, torch)
     line = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic", "mfma_frac_of_peak": tflops / PEAK_BF16_TFLOPS,
         "config": {"workload": "configs[1]: SD3-shaped MMDiT branch, 1024x1024, 24 blocks, hidden 1536, "
                                "4096+333 tokens, batch 1, one denoiser forward", "algorithmic_tflop_per_step": flops / 1e12},
-        "roofline": roofline, "guidance_pass_roofline": guidance, "kernels": kernels, "setup_s": round(setup_s, 1),
+        "roofline": roofline, "guidance_pass_roofline": guidance, "kernels": kernels, "other_workloads": secondary, "setup_s": round(setup_s, 1),
         "device": torch.cuda.get_device_name(0),
     }
     if not args.no_cpu_baseline:

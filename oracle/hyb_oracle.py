@@ -215,6 +215,36 @@ def mmdit_block(x_img, x_txt, temb, w, heads, eps=1e-6, return_parts=False):
     return out['img'], out['txt']
 
 
+def mmdit_block_rows(x_img, x_txt, temb, w, heads, img_rows, txt_rows, eps=1e-6):
+    """The same block, evaluated only for the listed token rows of each stream (sampled outputs at
+    sizes where the full block is too slow): keys and values are formed for ALL tokens, queries,
+    attention, projections and MLP only for the selected rows (everything after the attention is
+    per token).  Returns (out_img[B, len(img_rows), D], out_txt[B, len(txt_rows), D])."""
+    xs = {'img': _f64(x_img), 'txt': _f64(x_txt)}
+    rows = {'img': np.asarray(img_rows, dtype=np.int64), 'txt': np.asarray(txt_rows, dtype=np.int64)}
+    temb = _f64(temb)
+    mods, ks, vs, qs = {}, [], [], []
+    for s in ('img', 'txt'):
+        mods[s] = adaln_modulation(temb, w[s]['ada_w'], w[s]['ada_b'], 6)
+        h = modulate(layer_norm(xs[s], eps), mods[s][0], mods[s][1])
+        y = linear(h, w[s]['qkv_w'], w[s]['qkv_b'])
+        q, k, v = (split_heads(part, heads) for part in np.split(y, 3, axis=-1))
+        qs.append(q[:, :, rows[s]])
+        ks.append(k)
+        vs.append(v)
+    o = attention(np.concatenate(qs, axis=2), np.concatenate(ks, axis=2), np.concatenate(vs, axis=2))
+    n_sel = len(rows['img'])
+    os_ = {'img': o[:, :n_sel], 'txt': o[:, n_sel:]}
+    out = {}
+    for s in ('img', 'txt'):
+        _, _, g1, sh2, sc2, g2 = mods[s]
+        x = xs[s][:, rows[s]] + g1[:, None, :] * linear(os_[s], w[s]['out_w'], w[s]['out_b'])
+        h2 = modulate(layer_norm(x, eps), sh2, sc2)
+        m = linear(gelu_tanh(linear(h2, w[s]['fc1_w'], w[s]['fc1_b'])), w[s]['fc2_w'], w[s]['fc2_b'])
+        out[s] = x + g2[:, None, :] * m
+    return out['img'], out['txt']
+
+
 def mmdit_embed(latent, ctx, t, P, patch):
     """Token / context / timestep embeddings of the branch forward."""
     x_img = linear(patchify(latent, patch), P['pe_w'], P['pe_b']) + _f64(P['pos'])[None]

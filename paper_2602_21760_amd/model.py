@@ -65,6 +65,17 @@ class MMDiT:
         self.out_tok = torch.empty(B, cfg.n_img, cfg.patch_dim, **act)
         self.v = torch.empty(B, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, **act)
 
+    def reconfigure(self, cfg, batch=None, pos_np=None):
+        """Re-allocate the activation buffers for another token count / batch of the SAME network
+        (weights are kept; a new positional table is needed when the image token count changes)."""
+        assert (cfg.hidden, cfg.heads, cfg.blocks, cfg.dtype) == (self.cfg.hidden, self.cfg.heads, self.cfg.blocks, self.cfg.dtype)
+        self.cfg = cfg
+        self.B = cfg.batch if batch is None else batch
+        if pos_np is not None:
+            self.pos = _dev(pos_np)
+        assert self.pos.shape[0] == cfg.n_img
+        self._alloc()
+
     def embed(self, latent, ctx, t):
         """latent: f32[B, Hh, Ww, C]; ctx: f32[B, Nt, ctx_dim]; t: f32[B] (device tensors)."""
         cfg, g = self.cfg, self.g

@@ -105,3 +105,34 @@ def test_cfg2_full_forward(hb, capsys):
     with capsys.disabled():
         print("  [cfg2 full] rel-L2 of v vs oracle: %.3e (%.0f s)" % (err, time.time() - t0), flush=True)
     assert err < TOL_BF16
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_block_2048_sampled_rows(hb, capsys):
+    """One joint block at the 2048 x 2048 shape (16384 image + 333 text tokens, hidden 1536): the GPU block
+    output is compared on sampled token rows that the oracle evaluates one by one (keys / values of all
+    16717 tokens, queries and everything after the attention for the sampled rows only)."""
+    from paper_2602_21760_amd import binding as B
+    cfg = synth.CFG4
+    D = cfg.hidden
+    w = synth.mmdit_block_weights(cfg, 0)
+    x_img = synth.normal(91, (1, cfg.n_img, D), 1.0, "f32")
+    x_txt = synth.normal(92, (1, cfg.n_txt, D), 1.0, "f32")
+    temb = synth.normal(93, (1, D), 1.0, "f32")
+    devw = {s: {n: dev(a, torch.bfloat16 if n.endswith("_w") else torch.float32) for n, a in w[s].items()} for s in w}
+    mod = torch.empty(1, 12 * D, device="cuda")
+    hb.hyb_adaln_modulation(torch.cat([devw["img"]["ada_w"], devw["txt"]["ada_w"]]).contiguous(),
+                            torch.cat([devw["img"]["ada_b"], devw["txt"]["ada_b"]]).contiguous(), dev(temb), mod)
+    desc = B.block_desc(1, cfg.n_img, cfg.n_txt, D, cfg.heads, B.HYB_BF16)
+    ws = torch.empty(hb.hyb_block_workspace_bytes(desc), device="cuda", dtype=torch.uint8)
+    xi, xt = dev(x_img), dev(x_txt)
+    hb.hyb_block_forward(desc, B.block_weights(devw["img"], devw["txt"]), xi, xt, mod, mod[:, 6 * D:], 12 * D, xi, xt, ws)
+    g_img, g_txt = host(xi), host(xt)
+    rng = np.random.default_rng(4)
+    ri = np.unique(np.concatenate([[0, 127, 128, cfg.n_img - 1], rng.integers(0, cfg.n_img, 56)]))
+    rt = np.unique(np.concatenate([[0, 255, 256, cfg.n_txt - 1], rng.integers(0, cfg.n_txt, 12)]))
+    with capsys.disabled():
+        print("  [cfg4 block] GPU done, oracle on %d + %d sampled rows ..." % (len(ri), len(rt)), flush=True)
+    r_img, r_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
+    assert rel_l2(g_img[:, ri], r_img) < TOL_BF16 and rel_l2(g_txt[:, rt], r_txt) < TOL_BF16
+    assert rel_l2(g_img[:, ri] - x_img[:, ri], r_img - x_img[:, ri]) < 5e-2

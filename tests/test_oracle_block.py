@@ -208,3 +208,13 @@ def test_sdxl_block_against_library_assembly():
     c = b + F.linear(u * F.gelu(gate), T(w["ff2_w"]), T(w["ff2_b"]))
     np.testing.assert_allclose(got, (xt + c).numpy(), rtol=1e-10, atol=1e-11)
     assert np.linalg.norm(got - x) / np.linalg.norm(x) > 0.05
+
+
+def test_block_rows_equals_full_block():
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 7, scale_w=10.0)
+    f_img, f_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+    ri, rt = [0, 3, 15, 7], [4, 0]
+    s_img, s_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
+    np.testing.assert_allclose(s_img, f_img[:, ri], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(s_txt, f_txt[:, rt], rtol=1e-11, atol=1e-12)
