@@ -42,6 +42,12 @@ typedef void __attribute__((address_space(3)))* lptr_t;
 
 __device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
 __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     // [buffer][K tile | V tile]
     __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * TILE_BYTES];
@@ -120,11 +126,16 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
                     if (key >= a.n_kv) s[kt][i] = -__builtin_inff();
                 }
         }
-        float mx = fmaxf(s[0][0], s[1][0]);
+        // v_max3_f32 directly: fmaxf() makes the compiler canonicalise every MFMA output first (one extra
+        // multiply per score), which costs more than the maxima themselves
+        float mx = s[0][0];
 #pragma unroll
-        for (int i = 1; i < 16; i += 3) mx = fmaxf(fmaxf(mx, s[0][i]), fmaxf(s[0][i + 1], s[0][i + 2]));
-#pragma unroll
-        for (int i = 1; i < 16; i += 3) mx = fmaxf(fmaxf(mx, s[1][i]), fmaxf(s[1][i + 1], s[1][i + 2]));
+        for (int i = 1; i < 16; i += 3) {
+            mx = max3(mx, s[0][i], s[0][i + 1]);
+            mx = max3(mx, s[0][i + 2], s[1][i]);
+            mx = max3(mx, s[1][i + 1], s[1][i + 2]);
+        }
+        mx = max3(mx, s[1][0], s[1][0]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
         const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
