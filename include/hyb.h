@@ -257,6 +257,33 @@ int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb_sdxl_block
 size_t hyb_sdxl_block_workspace_bytes(const hyb_sdxl_block_desc* desc);
 
 /* ------------------------------------------------------------------------------------------
+ * Adaptive parallelism switching (Sec. 4.3, Eq. 2-3, Alg. 1): host-side controller, no device work.
+ * Steps are counted upwards in sampling order, i = 0 .. total_steps - 1.  With the discrepancy M_i
+ * of step i (Eq. 1, from hyb_branch_discrepancy / hyb_cfg_disc_euler), the slope over the last
+ * `window` steps is read as the rate of decline G_i = (M[i - window] - M[i]) / window; tau1 is the
+ * first i >= window with 0 <= G_i < g_slope, capped by tau_cap (and set to tau_cap when step
+ * tau_cap is reached without the test firing); tau2 = tau1 + k.  Stage of step i: 0 = warm-up
+ * (i <= tau1 or tau1 not yet known), 1 = parallelism (tau1 < i < tau2), 2 = fully-connecting.
+ * The paper's settings: SDXL window 12, g_slope 0.4e-3, k 5, tau_cap 15; SD3 15, 0.1e-3, 5, 40.
+ * ---------------------------------------------------------------------------------------- */
+#define HYB_SWITCH_MAX_STEPS 1024
+typedef struct {
+    int total_steps, window, tau_cap, k;
+    float g_slope;
+    int step;                 /* number of discrepancies pushed so far */
+    int tau1, tau2;           /* -1 until determined */
+    double history[HYB_SWITCH_MAX_STEPS];
+} hyb_switch_state;
+
+/* state: HOST memory owned by the caller. */
+int hyb_switch_init(hyb_switch_state* state, int total_steps, int window, float g_slope, int tau_cap, int k);
+/* Record M of the next step (call once per step, in order; the value is ignored once tau1 is known);
+ * *stage (may be NULL) receives the stage of that step. */
+int hyb_switch_push(hyb_switch_state* state, float discrepancy, int* stage);
+/* Stage of an arbitrary step under the boundaries known so far. */
+int hyb_switch_stage(const hyb_switch_state* state, int step);
+
+/* ------------------------------------------------------------------------------------------
  * Optional per-launch timing, for benchmarks (callers that measure, not the paper's method).
  * While enabled, every kernel launch of the library is bracketed by two events on its stream.
  * hyb_trace_enable(1) clears earlier records.  hyb_trace_summary waits for the recorded events

@@ -51,6 +51,15 @@ class SdxlBlockWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in SDXL_WEIGHT_FIELDS]
 
 
+HYB_SWITCH_MAX_STEPS = 1024
+
+
+class SwitchState(C.Structure):
+    _fields_ = [("total_steps", C.c_int), ("window", C.c_int), ("tau_cap", C.c_int), ("k", C.c_int),
+                ("g_slope", C.c_float), ("step", C.c_int), ("tau1", C.c_int), ("tau2", C.c_int),
+                ("history", C.c_double * HYB_SWITCH_MAX_STEPS)]
+
+
 _vp, _i, _f, _sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
 SIGNATURES = {
     "hyb_version": (C.c_int, []),
@@ -77,6 +86,9 @@ SIGNATURES = {
     "hyb_layernorm_affine": (_i, [_vp, _vp, _vp, _vp, _i, _i, _f, _i, _vp]),
     "hyb_sdxl_block_forward": (_i, [C.POINTER(SdxlBlockDesc), C.POINTER(SdxlBlockWeights), _vp, _vp, _vp, _vp, _sz, _vp]),
     "hyb_sdxl_block_workspace_bytes": (_sz, [C.POINTER(SdxlBlockDesc)]),
+    "hyb_switch_init": (_i, [C.POINTER(SwitchState), _i, _i, _f, _i, _i]),
+    "hyb_switch_push": (_i, [C.POINTER(SwitchState), _f, C.POINTER(C.c_int)]),
+    "hyb_switch_stage": (_i, [C.POINTER(SwitchState), _i]),
     "hyb_trace_enable": (_i, [_i]),
     "hyb_trace_summary": (_i, [C.c_char_p, _sz]),
 }
@@ -317,3 +329,19 @@ def hyb_sdxl_block_forward(desc, weights, x_in, ctx, x_out, workspace):
     _check(lib().hyb_sdxl_block_forward(C.byref(desc), C.byref(weights), _p(x_in, torch.float32), _p(ctx),
                                         _p(x_out, torch.float32), _p(workspace), _nbytes(workspace), _stream()))
     return x_out
+
+
+def hyb_switch_init(total_steps, window, g_slope, tau_cap, k):
+    st = SwitchState()
+    _check(lib().hyb_switch_init(C.byref(st), total_steps, window, g_slope, tau_cap, k))
+    return st
+
+
+def hyb_switch_push(state, discrepancy):
+    stage = C.c_int(-1)
+    _check(lib().hyb_switch_push(C.byref(state), discrepancy, C.byref(stage)))
+    return stage.value
+
+
+def hyb_switch_stage(state, step):
+    return lib().hyb_switch_stage(C.byref(state), step)
