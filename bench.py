@@ -19,6 +19,11 @@ if ROOT not in sys.path:
 METRIC = "ms per denoiser step + TFLOP/s (MFMA %), SD3-shaped MMDiT branch at 1024²"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM-side bytes per launch from the rocprofv3 PMC runs recorded in profiles/pmc_hbm_traffic_cfg2_kernels.md
+# (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain 1 GiB copy gives on this counter set)
+TRAFFIC_BYTES = {"attention_mfma": 256.4e6, "guidance_pass": 806.1e6,
+                 "gemm_mfma_128x128.epi4.n4608.k1536": 252.3e6, "gemm_mfma_128x128.epi1.n6144.k1536": 249.0e6,
+                 "gemm_mfma_128x128.epi3.n1536.k6144": 577.0e6}
 
 
 def cpu_baseline(cfg, synth):
@@ -68,7 +73,8 @@ def guidance_roofline(hb, torch, steps):
     gbs = tr["work"] / tr["launches"] / (us * 1e-6) / 1e9
     out = {"kernel": "guidance_pass", "shape": "batch 256 x 262144 elements", "bound": "hbm", "achieved": gbs,
            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "us_per_launch": us,
-           "bytes_per_element": 12, "traffic": None}
+           "bytes_per_element": 12, "traffic": TRAFFIC_BYTES["guidance_pass"],
+           "algorithmic_bytes": tr["work"] / tr["launches"]}
     # real latent shapes (latency-bound): time in microseconds
     real = {}
     for name, ne in (("sd3_1024", 262144), ("sd3_2048", 1048576), ("sdxl_1024", 65536)):
@@ -199,7 +205,7 @@ def main():
     d = flop_kernels[dom]
     ach = d["work"] / d["launches"] / (d["ms"] / d["launches"] * 1e-3) / 1e12
     roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom),
                 "us_per_launch": d["ms"] / d["launches"] * 1e3, "flops_per_launch": d["work"] / d["launches"]}
 
     guidance = guidance_roofline(hb, torch, max(args.steps, 10))
