@@ -132,8 +132,25 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
     constexpr int CHUNKS_PER_ROW = (GEGLU ? BN / 2 : BN) / CHUNK_ELEMS;
     constexpr int SE = F32OUT ? 4 : 2;                  // bytes per staged element
+    constexpr int ITERS = ROWS_PER_PASS * CHUNKS_PER_ROW / 256;   // 16-byte chunks per thread per pass
 #pragma unroll
     for (int pass = 0; pass < NPASS; pass++) {
+        // gate * y + residual: fetch this pass's residual chunks first, so that their latency overlaps the
+        // staging (loading them one by one between the stores serialises on every load: out may alias res)
+        f32x4 resv[EPI == EPI_GATE_RES ? ITERS : 1];
+        if constexpr (EPI == EPI_GATE_RES) {
+#pragma unroll
+            for (int j = 0; j < ITERS; j++) {
+                const int c = tid + 256 * j;
+                const int r = row0 + pass * ROWS_PER_PASS + c / CHUNKS_PER_ROW, f = col0 + (c % CHUNKS_PER_ROW) * CHUNK_ELEMS;
+                resv[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (r < m && f < n) {
+                    const size_t o = (size_t)r * n + f;
+                    resv[j] = *reinterpret_cast<const f32x4*>(p.res + o);
+                    if (p.res2) resv[j] += *reinterpret_cast<const f32x4*>(p.res2 + o);
+                }
+            }
+        }
         if (NPASS == 1 || wt == pass) {
 #pragma unroll
             for (int tm = 0; tm < 2; tm++) {
@@ -172,8 +189,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
             }
         }
         __syncthreads();
-#pragma unroll 4
-        for (int c = tid; c < ROWS_PER_PASS * CHUNKS_PER_ROW; c += 256) {
+#pragma unroll
+        for (int j = 0; j < ITERS; j++) {
+            const int c = tid + 256 * j;
             const int trow = c / CHUNKS_PER_ROW, ch = c % CHUNKS_PER_ROW;
             const int r = row0 + pass * ROWS_PER_PASS + trow;
             const int f = col0 + ch * CHUNK_ELEMS;
@@ -198,9 +216,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
             } else if constexpr (EPI == EPI_GATE_RES) {
                 const size_t o = (size_t)r * n + f;
-                f32x4 v = *reinterpret_cast<const f32x4*>(srcp) + *reinterpret_cast<const f32x4*>(p.res + o);
-                if (p.res2) v += *reinterpret_cast<const f32x4*>(p.res2 + o);
-                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = v;
+                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = *reinterpret_cast<const f32x4*>(srcp) + resv[j];
             } else {
                 OT* dst = static_cast<OT*>(p.out) + (size_t)r * n + f;
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
