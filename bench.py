@@ -151,7 +151,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-secondary", action="store_true", help="skip the other workload shapes")
+    ap.add_argument("--secondary", action="store_true",
+                    help="also time the other workload shapes (guided step, 2048x2048, U-Net stages); off by default "
+                         "so that a kernel trace of the default command holds one shape per kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the two guidance branches are batched or run "
@@ -210,7 +212,7 @@ def main():
 
     guidance = guidance_roofline(hb, torch, max(args.steps, 10))
     secondary = {}
-    if not args.no_secondary:
+    if args.secondary:
         secondary = secondary_workloads(m, hb, model, synth, torch)
         del m
         torch.cuda.empty_cache()

@@ -27,6 +27,8 @@
 // and not stored.  The reduction order is fixed: results are deterministic and batch-invariant.
 #include "attention.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int BQ = 128;
@@ -46,6 +48,47 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
+}
+
+// max(x, x of lane ^ 32): v_permlane32_swap exchanges the upper 32 lanes of its first operand with the
+// lower 32 lanes of its second; with both holding x, one of them then carries the lower half's values in
+// both halves and the other the upper half's, so their maximum is the maximum over the pair of lanes.
+__device__ __forceinline__ float max_with_other_half(float x) {
+    float p = x, q = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(p), "+v"(q));
+    return max3(p, q, q);
+}
+
+// Transposing LDS reads of the V^T fragments of 32 output features (DT) for the four 16-key groups of a tile,
+// written as asm so that they can be issued long before their use: the compiler neither tracks them nor puts
+// a wait for the direct-to-LDS copies of the NEXT tile (other buffer) in front of them.  lds_wait() below
+// must stand between these reads and the first use of their results.
+template <int BUF, int DT>
+__device__ __forceinline__ void v_frags(const unsigned (&vbase)[8], bf16x4 (&vh)[2][2][2]) {
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int hf = 0; hf < 2; hf++) {
+            const int d0 = (4 * DT) ^ (4 * kt + 2 * hf);
+            const int off = BUF * 2 * TILE_BYTES + (kt * 32 + hf * 16) * ROWB;
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][0]) : "v"(vbase[d0]), "i"(off));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][1]) : "v"(vbase[d0 ^ 1]), "i"(off + 8 * ROWB));
+        }
+}
+
+// Waits for every outstanding LDS read; the fragments pass through it as operands, so nothing that uses
+// (or copies) them can be scheduled before the wait.
+__device__ __forceinline__ void lds_wait(bf16x4 (&vh)[2][2][2], bf16x8 (&vf)[2][2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(vh[0][0][0]), "+v"(vh[0][0][1]), "+v"(vh[0][1][0]), "+v"(vh[0][1][1]),
+                   "+v"(vh[1][0][0]), "+v"(vh[1][0][1]), "+v"(vh[1][1][0]), "+v"(vh[1][1][1]));
+#pragma unroll
+    for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+        for (int hf = 0; hf < 2; hf++) {
+            const bf16x4 lo = vh[kt][hf][0], hi = vh[kt][hf][1];
+            vf[kt][hf] = bf16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
 }
 
 __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
@@ -95,28 +138,59 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     const int v_key = 4 * g + sl / 4;                                  // + kt*32 + hf*16 (+8)
     const int v_feat = 16 * ((lane / 16) % 2) + 4 * (sl % 4);          // + dt*32
 
-    const int nt = (a.n_kv + BKV - 1) / BKV;
-    issue(0, 0);
-    for (int t = 0; t < nt; t++) {
-        const int cur = t & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile t has landed
-        __builtin_amdgcn_s_barrier();                      // ... everyone's; and buffer cur^1 is free again
-        if (t + 1 < nt) issue(t + 1, cur ^ 1);
-        const unsigned char* ks = smem[cur];
-        const unsigned char* vs = ks + TILE_BYTES;
+    // Per-lane LDS addresses, hoisted out of the tile loop.  The XOR swizzle makes the slot of a read
+    // (lane part) ^ (compile-time part D); the lane part is folded into 4 (K) and 8 (V) base addresses, one
+    // per value of D, and everything else (tile row block, operand, buffer) is an immediate offset.
+    const unsigned lds0 = (unsigned)(size_t)(lptr_t)&smem[0][0];
+    const unsigned char* kbase[4];
+    unsigned vbase[8];
+    {
+        const int kb = (g ^ lq ^ (lq >> 3)) & 7;
+#pragma unroll
+        for (int j = 0; j < 4; j++) kbase[j] = &smem[0][0] + lq * ROWB + ((kb ^ (2 * j)) * 16);
+        const int vb = ((v_feat / 8) ^ v_key) & 7;
+#pragma unroll
+        for (int d = 0; d < 8; d++) vbase[d] = lds0 + TILE_BYTES + v_key * ROWB + ((vb ^ d) * 16) + (v_feat % 8) * 2;
+    }
 
+    const int nt = (a.n_kv + BKV - 1) / BKV;
+    auto tile = [&](int t, auto buf_tag) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        constexpr int BUF_OFF = BUF * 2 * TILE_BYTES;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile t has landed
+        __builtin_amdgcn_s_barrier();                      // ... everyone's; and the other buffer is free again
+        if (t + 1 < nt) issue(t + 1, BUF ^ 1);
+
+        // S^T = K Q^T: two accumulation chains (keys 0..31 / 32..63) interleaved; the K fragments flow through
+        // a ring of four so that four LDS reads are always in flight ahead of the MFMA that needs them.
+        auto k_frag = [&](int j) {
+            const int kt = j & 1, kk = j >> 1;
+            return *reinterpret_cast<const bf16x8*>(kbase[(kk ^ (2 * kt)) & 3] + BUF_OFF + kt * 32 * ROWB);
+        };
+        bf16x8 ring[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) ring[j] = k_frag(j);
         f32x16 s[2];
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++) {
+        for (int i = 0; i < 16; i++) s[0][i] = s[1][i] = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; i++) s[kt][i] = 0.f;
-            const int r = kt * 32 + lq;
-#pragma unroll
-            for (int kk = 0; kk < 4; kk++) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + r * ROWB + (((kk * 2 + g) ^ swz(r)) * 16));
-                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[kt], 0, 0, 0);
-            }
+        for (int j = 0; j < 8; j++) {
+            s[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[j & 3], qf[j >> 1], s[j & 1], 0, 0, 0);
+            if (j + 4 < 8) ring[j & 3] = k_frag(j + 4);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+
+        // V^T fragments of the first 32 output features: issued now, consumed after the softmax
+        bf16x4 vh[2][2][2][2];
+        bf16x8 vf[2][2][2];
+        v_frags<BUF, 0>(vbase, vh[0]);
+
         if (t == nt - 1 && (a.n_kv % BKV) != 0) {
 #pragma unroll
             for (int kt = 0; kt < 2; kt++)
@@ -135,8 +209,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
             mx = max3(mx, s[0][i + 2], s[1][i]);
             mx = max3(mx, s[1][i + 1], s[1][i + 2]);
         }
-        mx = max3(mx, s[1][0], s[1][0]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = max_with_other_half(max3(mx, s[1][0], s[1][0]));
         // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
         const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
         if (__any(grow)) {
@@ -155,6 +228,14 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         for (int kt = 0; kt < 2; kt++)
 #pragma unroll
             for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
+
+        // O^T += V^T P^T (the fragments of the other 32 features take the registers the scores leave)
+        v_frags<BUF, 1>(vbase, vh[1]);
+        lds_wait(vh[0], vf[0]);
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+            for (int hf = 0; hf < 2; hf++) o[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[0][kt][hf], pb[kt][hf], o[0], 0, 0, 0);
         const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
@@ -165,21 +246,16 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
                     const bf16x2 pr = {pb[kt][hf][j], pb[kt][hf][j + 1]};
                     l_run = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l_run, false);
                 }
-
+        lds_wait(vh[1], vf[1]);
 #pragma unroll
-        for (int dt = 0; dt < 2; dt++)
+        for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-            for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-                for (int hf = 0; hf < 2; hf++) {
-                    const int key = kt * 32 + hf * 16 + v_key, feat = dt * 32 + v_feat;
-                    const unsigned char* p0 = vs + key * ROWB + (((feat / 8) ^ swz(key)) * 16) + (feat % 8) * 2;
-                    const unsigned char* p1 = vs + (key + 8) * ROWB + (((feat / 8) ^ swz(key + 8)) * 16) + (feat % 8) * 2;
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p0);
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)p1);
-                    const bf16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kt][hf], o[dt], 0, 0, 0);
-                }
+            for (int hf = 0; hf < 2; hf++) o[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][kt][hf], pb[kt][hf], o[1], 0, 0, 0);
+    };
+    issue(0, 0);
+    for (int t = 0; t < nt; t += 2) {
+        tile(t, std::integral_constant<int, 0>{});
+        if (t + 1 < nt) tile(t + 1, std::integral_constant<int, 1>{});
     }
 
     if (qrow >= a.n_q) return;
