@@ -4,7 +4,9 @@
 // A workgroup of 4 waves owns 128 query rows of one (batch, head); each wave owns 32 of them.
 // Keys / values are streamed 64 at a time through double-buffered LDS tiles shared by the waves,
 // copied global -> LDS by 16-byte direct-to-LDS loads (no VGPR staging); rows are 128 bytes,
-// unpadded, with their 16-byte slots XOR-swizzled by (row ^ row >> 3) & 7 against bank conflicts.
+// unpadded, with their 16-byte slots XOR-swizzled against bank conflicts: K rows (read one row per
+// lane, 16 bytes each) by (row ^ row >> 3) & 7, V rows (read by transposing loads, 8 keys x 64 bytes
+// per instruction) by 4 * (row >> 1 & 1).
 // Both contractions run on v_mfma_f32_32x32x16_bf16 in TRANSPOSED form:
 //   S^T = K Q^T   (A operand: a K row per lane from LDS; B operand: the lane's query row, kept in
 //                  registers for the whole kernel)
@@ -18,6 +20,8 @@
 // and the matching V^T fragment comes from two transposing LDS reads (ds_read_b64_tr_b16) of the V
 // tile kept in its natural [key][feature] layout: in a group of 16 lanes, lane s points at 4
 // features of key (s / 4) and lane i receives feature (i) of 4 consecutive keys.
+// The K fragments of a tile flow through a ring of four reads that run ahead of the MFMAs; the V^T
+// fragments of the first 32 output features are requested before the softmax and used after it.
 // Softmax runs in fp32 with exp2 and the scale folded into one FMA.  The running maximum is only
 // advanced (and the output accumulator rescaled) when some row's maximum grew by more than 2^8;
 // until then exponentials are taken against the older maximum (values up to 2^8, exact same
@@ -42,7 +46,10 @@ typedef bf16x4 __attribute__((address_space(3)))* lds_bf16x4_ptr;
 typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
-__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
+__device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }   // K tile: row-per-lane 16-byte reads
+// V tile: a transposing read touches 8 consecutive keys x 64 bytes, 4 keys per half wave; keys r and r + 2
+// sit 256 bytes (one sweep of the banks) apart, so they go to opposite 64-byte halves of their rows.
+__device__ __forceinline__ int swz_v(int r) { return ((r >> 1) & 1) * 4; }
 
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
@@ -64,15 +71,14 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 // a wait for the direct-to-LDS copies of the NEXT tile (other buffer) in front of them.  lds_wait() below
 // must stand between these reads and the first use of their results.
 template <int BUF, int DT>
-__device__ __forceinline__ void v_frags(const unsigned (&vbase)[8], bf16x4 (&vh)[2][2][2]) {
+__device__ __forceinline__ void v_frags(unsigned vaddr, bf16x4 (&vh)[2][2][2]) {
 #pragma unroll
     for (int kt = 0; kt < 2; kt++)
 #pragma unroll
         for (int hf = 0; hf < 2; hf++) {
-            const int d0 = (4 * DT) ^ (4 * kt + 2 * hf);
             const int off = BUF * 2 * TILE_BYTES + (kt * 32 + hf * 16) * ROWB;
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][0]) : "v"(vbase[d0]), "i"(off));
-            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][1]) : "v"(vbase[d0 ^ 1]), "i"(off + 8 * ROWB));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][0]) : "v"(vaddr), "i"(off));
+            asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[kt][hf][1]) : "v"(vaddr), "i"(off + 8 * ROWB));
         }
 }
 
@@ -97,9 +103,22 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int lq = lane % 32, g = lane / 32;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Workgroups go round-robin to the 8 XCDs (each with its own L2) in launch order.  When the number of
+    // (batch, head) pairs is a multiple of 8, pair p is served entirely by XCD p % 8, so its K and V stay in
+    // one L2 instead of being fetched into all eight.
+    const int qblocks = (a.n_q + BQ - 1) / BQ, pairs = a.batch * a.heads;
+    int pair, qb;
+    if (pairs % 8 == 0) {
+        const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+        pair = xcd + 8 * (j / qblocks);
+        qb = j % qblocks;
+    } else {
+        pair = blockIdx.x / qblocks;
+        qb = blockIdx.x % qblocks;
+    }
+    const int h = pair % a.heads, b = pair / a.heads;
     const size_t bh = (size_t)b * a.heads + h;
-    const int qrow = blockIdx.x * BQ + wave * 32 + lq;
+    const int qrow = qb * BQ + wave * 32 + lq;
     const bf16_t* qp = static_cast<const bf16_t*>(a.q) + (bh * a.n_q + min(qrow, a.n_q - 1)) * 64;
     const bf16_t* kp = static_cast<const bf16_t*>(a.k) + bh * a.n_kv * 64;
     const bf16_t* vp = static_cast<const bf16_t*>(a.v) + bh * a.n_kv * 64;
@@ -109,16 +128,16 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     for (int kk = 0; kk < 4; kk++) qf[kk] = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + g * 8);
 
     // Tile copy: 16 chunks of 1 KB (8 rows) per tile pair, 4 per wave: chunks w, w+4 of K and of V.
-    // Lane i fills slot i % 8 of row i / 8 of its chunk with feature vector (slot ^ swz(row)).
+    // Lane i fills slot i % 8 of row i / 8 of its chunk with feature vector (slot ^ swz(row)) (V: swz_v).
     const int cp_row = lane / 8;
     auto issue = [&](int t, int buf) {
 #pragma unroll
         for (int c = 0; c < 2; c++) {
             const int r = (wave + 4 * c) * 8 + cp_row;                       // row inside the tile
             const size_t grow = (size_t)min(t * BKV + r, a.n_kv - 1);        // clamped; masked in the scores
-            const int fv = (lane % 8) ^ swz(r);
+            const int fk = (lane % 8) ^ swz(r), fv = (lane % 8) ^ swz_v(r);
             unsigned char* dst = smem[buf] + (wave + 4 * c) * 1024;
-            __builtin_amdgcn_global_load_lds((gptr_t)(kp + grow * 64 + fv * 8), (lptr_t)dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(kp + grow * 64 + fk * 8), (lptr_t)dst, 16, 0, 0);
             __builtin_amdgcn_global_load_lds((gptr_t)(vp + grow * 64 + fv * 8), (lptr_t)(dst + TILE_BYTES), 16, 0, 0);
         }
     };
@@ -139,18 +158,19 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     const int v_feat = 16 * ((lane / 16) % 2) + 4 * (sl % 4);          // + dt*32
 
     // Per-lane LDS addresses, hoisted out of the tile loop.  The XOR swizzle makes the slot of a read
-    // (lane part) ^ (compile-time part D); the lane part is folded into 4 (K) and 8 (V) base addresses, one
-    // per value of D, and everything else (tile row block, operand, buffer) is an immediate offset.
+    // (lane part) ^ (compile-time part D) for K; the lane part is folded into 4 base addresses, one per value
+    // of D (V: one per half of the features), and everything else (tile row block, operand, buffer) is an
+    // immediate offset.
     const unsigned lds0 = (unsigned)(size_t)(lptr_t)&smem[0][0];
     const unsigned char* kbase[4];
-    unsigned vbase[8];
+    unsigned vbase[2];   // by half of the output features; swz_v depends on the lane's key only
     {
         const int kb = (g ^ lq ^ (lq >> 3)) & 7;
 #pragma unroll
         for (int j = 0; j < 4; j++) kbase[j] = &smem[0][0] + lq * ROWB + ((kb ^ (2 * j)) * 16);
-        const int vb = ((v_feat / 8) ^ v_key) & 7;
 #pragma unroll
-        for (int d = 0; d < 8; d++) vbase[d] = lds0 + TILE_BYTES + v_key * ROWB + ((vb ^ d) * 16) + (v_feat % 8) * 2;
+        for (int dt = 0; dt < 2; dt++)
+            vbase[dt] = lds0 + TILE_BYTES + v_key * ROWB + (((4 * dt + v_feat / 8) ^ swz_v(v_key)) * 16) + (v_feat % 8) * 2;
     }
 
     const int nt = (a.n_kv + BKV - 1) / BKV;
@@ -189,7 +209,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         // V^T fragments of the first 32 output features: issued now, consumed after the softmax
         bf16x4 vh[2][2][2][2];
         bf16x8 vf[2][2][2];
-        v_frags<BUF, 0>(vbase, vh[0]);
+        v_frags<BUF, 0>(vbase[0], vh[0]);
 
         if (t == nt - 1 && (a.n_kv % BKV) != 0) {
 #pragma unroll
@@ -230,7 +250,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
             for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
 
         // O^T += V^T P^T (the fragments of the other 32 features take the registers the scores leave)
-        v_frags<BUF, 1>(vbase, vh[1]);
+        v_frags<BUF, 1>(vbase[1], vh[1]);
         lds_wait(vh[0], vf[0]);
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
@@ -280,7 +300,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 }  // namespace
 
 int hyb_launch_attention_mfma(const AttnArgs& a, hipStream_t st) {
-    dim3 grid((a.n_q + BQ - 1) / BQ, a.heads, a.batch), block(256);
+    dim3 grid(((a.n_q + BQ - 1) / BQ) * a.heads * a.batch), block(256);
     HybTraceScope trace("attention_mfma", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
     hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, a);
     return hyb_check_launch("attention_mfma");
