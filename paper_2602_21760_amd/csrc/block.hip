@@ -8,6 +8,9 @@
 
 int hyb_launch_layernorm(const float* x, const float* shift, const float* scale, size_t mod_stride, void* out,
                          int batch, int tokens, int hidden, float eps, hyb_dtype out_dtype, bool affine, hipStream_t st);
+int hyb_launch_layernorm_pair(const float* const x[2], const float* const shift[2], const float* const scale[2],
+                              size_t mod_stride, void* const out[2], int batch, const int tokens[2], int hidden,
+                              float eps, hyb_dtype out_dtype, hipStream_t st);
 
 namespace {
 
@@ -112,8 +115,11 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     };
 
     // 1. h = LN(x)(1 + scale1) + shift1
-    for (int s = 0; s < 2; s++)
-        if ((rc = hyb_launch_layernorm(xin[s], mod[s], mod[s] ? mod[s] + D : nullptr, mod_stride, h[s], B, ntok[s], D, d.ln_eps, dt, false, st))) return rc;
+    {
+        const float* sh[2] = {mod[0], mod[1]};
+        const float* sc[2] = {mod[0] ? mod[0] + D : nullptr, mod[1] ? mod[1] + D : nullptr};
+        if ((rc = hyb_launch_layernorm_pair(xin, sh, sc, mod_stride, h, B, ntok, D, d.ln_eps, dt, st))) return rc;
+    }
     // 2. q, k, v = h Wqkv^T + b, scattered head-major into the joint (image first) sequence
     {
         GemmGroup g = group(3 * D, D);
@@ -143,8 +149,11 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
         if ((rc = hyb_launch_gemm(g, dt, HYB_F32, EPI_GATE_RES, st))) return rc;
     }
     // 5. h2 = LN(x)(1 + scale2) + shift2
-    for (int s = 0; s < 2; s++)
-        if ((rc = hyb_launch_layernorm(xout[s], mod[s] ? mod[s] + 3 * D : nullptr, mod[s] ? mod[s] + 4 * D : nullptr, mod_stride, h[s], B, ntok[s], D, d.ln_eps, dt, false, st))) return rc;
+    {
+        const float* sh[2] = {mod[0] ? mod[0] + 3 * D : nullptr, mod[1] ? mod[1] + 3 * D : nullptr};
+        const float* sc[2] = {mod[0] ? mod[0] + 4 * D : nullptr, mod[1] ? mod[1] + 4 * D : nullptr};
+        if ((rc = hyb_launch_layernorm_pair(xout, sh, sc, mod_stride, h, B, ntok, D, d.ln_eps, dt, st))) return rc;
+    }
     // 6. u = GELUtanh(h2 W1^T + b1)
     {
         GemmGroup g = group(d.mlp_ratio * D, D);

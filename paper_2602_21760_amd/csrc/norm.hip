@@ -16,13 +16,37 @@ namespace {
 // ------------------------------------------------------------------------------------------
 constexpr int kLnMaxVec = 8;   // float4 per lane -> hidden <= 8 * 64 * 4 = 2048
 
+// Up to two independent row sets (the image and the text stream of a joint block) share one launch:
+// workgroups [0, blocks0) serve set 0, the rest set 1.
+struct LnSet {
+    const float* x;
+    const float* shift;
+    const float* scale;
+    void* out;
+    size_t mod_stride;
+    int rows, tokens;
+};
+struct LnArgs {
+    LnSet s[2];
+    int blocks0;
+    int hidden;
+    float eps;
+};
+
 template <typename OT, bool AFFINE>
-__global__ __launch_bounds__(256) void layernorm_kernel(const float* __restrict__ x, const float* __restrict__ shift,
-                                                        const float* __restrict__ scale, size_t mod_stride,
-                                                        OT* __restrict__ out, int rows, int tokens, int hidden, float eps) {
+__global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
     const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
-    const int row = blockIdx.x * 4 + wave;
-    if (row >= rows) return;
+    const int set = blockIdx.x >= a.blocks0 ? 1 : 0;
+    const LnSet& p = a.s[set];
+    const int row = (blockIdx.x - (set ? a.blocks0 : 0)) * 4 + wave;
+    if (row >= p.rows) return;
+    const float* __restrict__ x = p.x;
+    const float* __restrict__ shift = p.shift;
+    const float* __restrict__ scale = p.scale;
+    OT* __restrict__ out = static_cast<OT*>(p.out);
+    const size_t mod_stride = p.mod_stride;
+    const int tokens = p.tokens, hidden = a.hidden;
+    const float eps = a.eps;
     const int nvec = hidden / 4;
     const f32x4* xr = reinterpret_cast<const f32x4*>(x + (size_t)row * hidden);
     f32x4 r[kLnMaxVec];
@@ -245,22 +269,51 @@ __global__ void convert_kernel(const float* in, OT* out, size_t n) {
 
 }  // namespace
 
+namespace {
+int launch_layernorm(const LnArgs& a, int blocks, double rows, hyb_dtype out_dtype, bool affine, hipStream_t st) {
+    dim3 grid(blocks), block(256);
+    HybTraceScope trace("layernorm", "byte", rows * a.hidden * (4 + hyb_dtype_size(out_dtype)), st);
+    if (out_dtype == HYB_F32) {
+        if (affine) hipLaunchKernelGGL((layernorm_kernel<float, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((layernorm_kernel<float, false>), grid, block, 0, st, a);
+    } else {
+        if (affine) hipLaunchKernelGGL((layernorm_kernel<bf16_t, true>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((layernorm_kernel<bf16_t, false>), grid, block, 0, st, a);
+    }
+    return hyb_check_launch("layernorm");
+}
+}  // namespace
+
 // Internal launcher shared with the block composition (affine = gamma/beta LayerNorm).
 int hyb_launch_layernorm(const float* x, const float* shift, const float* scale, size_t mod_stride, void* out,
                          int batch, int tokens, int hidden, float eps, hyb_dtype out_dtype, bool affine,
                          hipStream_t st) {
     const int rows = batch * tokens;
     if (rows == 0) return HYB_OK;
-    dim3 grid((rows + 3) / 4), block(256);
-    HybTraceScope trace("layernorm", "byte", (double)rows * hidden * (4 + hyb_dtype_size(out_dtype)), st);
-    if (out_dtype == HYB_F32) {
-        if (affine) hipLaunchKernelGGL((layernorm_kernel<float, true>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
-        else hipLaunchKernelGGL((layernorm_kernel<float, false>), grid, block, 0, st, x, shift, scale, mod_stride, (float*)out, rows, tokens, hidden, eps);
-    } else {
-        if (affine) hipLaunchKernelGGL((layernorm_kernel<bf16_t, true>), grid, block, 0, st, x, shift, scale, mod_stride, (bf16_t*)out, rows, tokens, hidden, eps);
-        else hipLaunchKernelGGL((layernorm_kernel<bf16_t, false>), grid, block, 0, st, x, shift, scale, mod_stride, (bf16_t*)out, rows, tokens, hidden, eps);
+    LnArgs a{};
+    a.s[0] = LnSet{x, shift, scale, out, mod_stride, rows, tokens};
+    a.blocks0 = (rows + 3) / 4;
+    a.hidden = hidden;
+    a.eps = eps;
+    return launch_layernorm(a, a.blocks0, rows, out_dtype, affine, st);
+}
+
+// Two modulated LayerNorms (no affine) of the same width in one launch; either set may be empty.
+int hyb_launch_layernorm_pair(const float* const x[2], const float* const shift[2], const float* const scale[2],
+                              size_t mod_stride, void* const out[2], int batch, const int tokens[2], int hidden,
+                              float eps, hyb_dtype out_dtype, hipStream_t st) {
+    LnArgs a{};
+    int blocks[2];
+    for (int i = 0; i < 2; i++) {
+        const int rows = batch * tokens[i];
+        a.s[i] = LnSet{x[i], shift[i], scale[i], out[i], mod_stride, rows, tokens[i] > 0 ? tokens[i] : 1};
+        blocks[i] = (rows + 3) / 4;
     }
-    return hyb_check_launch("layernorm");
+    if (blocks[0] + blocks[1] == 0) return HYB_OK;
+    a.blocks0 = blocks[0];
+    a.hidden = hidden;
+    a.eps = eps;
+    return launch_layernorm(a, blocks[0] + blocks[1], (double)batch * (tokens[0] + tokens[1]), out_dtype, false, st);
 }
 
 size_t hyb_groupnorm_scratch_bytes(int batch, int groups) {
