@@ -138,6 +138,22 @@ class GuidedSampler:
                               disc_l1=self.disc[0, i:i + 1], disc_l2=self.disc[1, i:i + 1], workspace=self.ws)
         return x
 
+    def sample(self, x, ctx2, sigmas, switch=None):
+        """All steps of a schedule (sigmas: T + 1 values).  With a switching state (hyb_switch_init), the
+        denoising discrepancy of every step (Eq. 1: the L1 ratio) is handed to the controller as soon as
+        the step's kernels have finished -- one 4-byte read-back per step, as the online rule of Alg. 1
+        needs the value before the next step -- and the stage the controller assigns to each step is
+        returned: this single-device build runs every step the same way and only records the decision."""
+        steps = len(sigmas) - 1
+        if self.disc.shape[1] < steps:
+            self.disc = torch.zeros(2, steps, device="cuda", dtype=torch.float32)
+        stages = []
+        for i in range(steps):
+            self.step(x, ctx2, float(sigmas[i]), float(sigmas[i + 1]), i)
+            if switch is not None:
+                stages.append(hb.hyb_switch_push(switch, float(self.disc[0, i].item())))
+        return x, stages
+
 
 class SDXLStage:
     """Device-resident weights + workspace of one SDXL-shaped transformer stage (see synth.SDXLStageConfig).

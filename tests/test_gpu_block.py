@@ -137,3 +137,31 @@ def test_reduced_bf16_forward_and_guided_loop(hb):
     g1, g2 = host(gs.disc[0, :T]), host(gs.disc[1, :T])
     print("disc L1 gpu/oracle:", g1, M1[:, 0], "L2:", g2, M2[:, 0])
     assert np.all(np.isfinite(g1)) and np.all(g1 > 0)
+
+
+def test_guided_loop_with_switching_controller(hb):
+    """The controller (Sec. 4.3, Alg. 1) fed online from the fused guidance pass, on a reduced fp32 model:
+    per-step discrepancies and the stage assigned to every step against the oracle's loop and rule."""
+    from paper_2602_21760_amd import model
+    cfg = synth.scaled(synth.CFG1, blocks=2, batch=2)
+    T, L, g_slope, tau_cap, k = 14, 3, 0.05, 9, 2
+    P = synth.mmdit_globals(cfg)
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    m = model.MMDiT(cfg, P, synth.mmdit_blocks(cfg))
+    gs = model.GuidedSampler(m, cfg.guidance)
+    sig = O.sigma_schedule(T, cfg.shift)
+    x = dev(lat).clone()
+    st = hb.hyb_switch_init(T, L, g_slope, tau_cap, k)
+    x, stages = gs.sample(x, dev(np.stack([ctx_c, ctx_u])), sig, switch=st)
+    blocks = list(synth.mmdit_blocks(cfg))
+    rx, M1, _ = O.sampling_loop(lat[None], ctx_c[None], ctx_u[None], P, lambda: blocks, cfg.heads, cfg.patch, T,
+                                cfg.shift, cfg.guidance)
+    assert rel_l2(host(x), rx[0]) < TOL_F32 * 10          # 14 steps of accumulated fp32 rounding
+    g1 = host(gs.disc[0, :T])
+    assert np.all(np.abs(g1 - M1[:, 0]) < TOL_DISC * M1[:, 0])
+    tau1, tau2 = O.switching_points(M1[:, 0], L, g_slope, tau_cap, k)
+    assert (st.tau1, st.tau2) == (tau1, tau2)
+    # the stage handed back when a step is pushed (warm-up until tau1 is known) is its final stage
+    assert stages == [O.stage_of(i, tau1, tau2) for i in range(T)]
+    assert [hb.hyb_switch_stage(st, i) for i in range(T)] == stages
+    print("M:", g1, "tau1, tau2:", tau1, tau2, "stages:", stages)
