@@ -125,6 +125,14 @@ def secondary_workloads(m, hb, model, synth, torch):
     t4 = torch.full((1,), 0.5, device="cuda")
     ms = timed(lambda: m.forward(l4, c4, t4), 3, 1, torch)
     out["configs[3] 2048x2048 branch forward"] = {"ms_per_step": round(ms, 3), "tflops": round(cfg4.flops_per_sample() / ms / 1e9, 1)}
+    # beyond the configs: the 2560 x 2560 shape of the paper's high-resolution study (25600 image tokens)
+    cfg6 = synth.CFG6
+    del l4, c4
+    m.reconfigure(cfg6, pos_np=synth.normal(4, (cfg6.n_img, cfg6.hidden), 0.02, cfg6.dtype))
+    lat6, ctx6, _ = synth.mmdit_inputs(cfg6)
+    l6, c6 = torch.from_numpy(lat6[None]).cuda(), torch.from_numpy(ctx6[None]).cuda()
+    ms = timed(lambda: m.forward(l6, c6, t4), 2, 1, torch)
+    out["2560x2560 branch forward"] = {"ms_per_step": round(ms, 3), "tflops": round(cfg6.flops_per_sample() / ms / 1e9, 1)}
     return out
 
 

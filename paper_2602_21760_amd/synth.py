@@ -90,6 +90,9 @@ CFG3 = MMDiTConfig("cfg3_sd3_guided_loop_bf16", blocks=24, hidden=1536, heads=24
                    latent_c=16, n_txt=333, ctx_dim=4096, batch=2, dtype="bf16", steps=28)
 CFG4 = MMDiTConfig("cfg4_sd3_2048_bf16", blocks=24, hidden=1536, heads=24, latent_hw=256,
                    latent_c=16, n_txt=333, ctx_dim=4096, batch=1, dtype="bf16")
+# the largest resolution of the paper's high-resolution study (Appendix, SD3 at 2560 x 2560): 25600 image tokens
+CFG6 = MMDiTConfig("cfg6_sd3_2560_bf16", blocks=24, hidden=1536, heads=24, latent_hw=320,
+                   latent_c=16, n_txt=333, ctx_dim=4096, batch=1, dtype="bf16")
 CFG5A = SDXLStageConfig("cfg5_sdxl_stageA", blocks=10, tokens=4096, channels=640, heads=10)
 CFG5B = SDXLStageConfig("cfg5_sdxl_stageB", blocks=20, tokens=1024, channels=1280, heads=20)
 CFG5_LATENT = (128, 128, 4)

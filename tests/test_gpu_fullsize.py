@@ -22,7 +22,7 @@ def hb():
     return binding
 
 
-@pytest.mark.parametrize("shape", [(2, 24, 4429), (1, 24, 16717)])
+@pytest.mark.parametrize("shape", [(2, 24, 4429), (1, 24, 16717), (1, 24, 25933)])
 def test_attention_full_size_sampled_rows(hb, shape):
     B, H, N = shape
     q, k, v = (synth.normal(60 + i, (B, H, N, 64), 1.0, "bf16") for i in range(3))
@@ -108,12 +108,12 @@ def test_cfg2_full_forward(hb, capsys):
 
 
 @pytest.mark.timeout(900)
-def test_cfg4_block_2048_sampled_rows(hb, capsys):
-    """One joint block at the 2048 x 2048 shape (16384 image + 333 text tokens, hidden 1536): the GPU block
-    output is compared on sampled token rows that the oracle evaluates one by one (keys / values of all
-    16717 tokens, queries and everything after the attention for the sampled rows only)."""
+@pytest.mark.parametrize("cfg", [synth.CFG4, synth.CFG6], ids=["cfg4_2048", "cfg6_2560"])
+def test_block_high_resolution_sampled_rows(hb, capsys, cfg):
+    """One joint block at the 2048 x 2048 and 2560 x 2560 shapes (16384 / 25600 image + 333 text tokens,
+    hidden 1536): the GPU block output is compared on sampled token rows that the oracle evaluates one by
+    one (keys / values of all tokens, queries and everything after the attention for the sampled rows only)."""
     from paper_2602_21760_amd import binding as B
-    cfg = synth.CFG4
     D = cfg.hidden
     w = synth.mmdit_block_weights(cfg, 0)
     x_img = synth.normal(91, (1, cfg.n_img, D), 1.0, "f32")
@@ -132,7 +132,7 @@ def test_cfg4_block_2048_sampled_rows(hb, capsys):
     ri = np.unique(np.concatenate([[0, 127, 128, cfg.n_img - 1], rng.integers(0, cfg.n_img, 56)]))
     rt = np.unique(np.concatenate([[0, 255, 256, cfg.n_txt - 1], rng.integers(0, cfg.n_txt, 12)]))
     with capsys.disabled():
-        print("  [cfg4 block] GPU done, oracle on %d + %d sampled rows ..." % (len(ri), len(rt)), flush=True)
+        print("  [%s block] GPU done, oracle on %d + %d sampled rows ..." % (cfg.name, len(ri), len(rt)), flush=True)
     r_img, r_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
     assert rel_l2(g_img[:, ri], r_img) < TOL_BF16 and rel_l2(g_txt[:, rt], r_txt) < TOL_BF16
     assert rel_l2(g_img[:, ri] - x_img[:, ri], r_img - x_img[:, ri]) < 5e-2
