@@ -157,6 +157,7 @@ typedef struct {
     int mlp_ratio;    /* MLP inner width = mlp_ratio * hidden */
     hyb_dtype dtype;
     float ln_eps;     /* 1e-6 for the MMDiT block */
+    int txt_pre_only; /* non-zero: the text stream only supplies keys and values (see hyb_block_forward) */
 } hyb_block_desc;
 
 typedef struct {
@@ -175,7 +176,11 @@ typedef struct { hyb_stream_weights img, txt; } hyb_block_weights;
  * x_img_in / x_img_out: device float[batch, n_img, hidden]; x_txt_*: device float[batch, n_txt,
  * hidden]; outputs may alias inputs.  mod_img, mod_txt: device float[batch, 6 * hidden] with row
  * stride mod_stride (from hyb_adaln_modulation).  workspace: device,
- * >= hyb_block_workspace_bytes(desc) bytes. */
+ * >= hyb_block_workspace_bytes(desc) bytes.
+ * desc->txt_pre_only (the last block of a model, whose text output nothing reads): the text
+ * stream is modulated and projected (its keys and values enter the attention) and that is all --
+ * no text queries, output projection or MLP; x_txt_out is NOT written.  The image output is the
+ * same as without the flag. */
 int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_weights* weights,
                       const float* x_img_in, const float* x_txt_in,
                       const float* mod_img, const float* mod_txt, size_t mod_stride,

@@ -182,14 +182,16 @@ def adaln_modulation(temb, ada_w, ada_b, chunks=6):
     return np.split(mod, chunks, axis=-1)
 
 
-def mmdit_block(x_img, x_txt, temb, w, heads, eps=1e-6, return_parts=False):
+def mmdit_block(x_img, x_txt, temb, w, heads, eps=1e-6, return_parts=False, txt_pre_only=False):
     """One joint image+text block.
 
     x_img[B, Ni, D], x_txt[B, Nt, D], temb[B, D]; w = {'img': {...}, 'txt': {...}} with
     ada_w/b [6D, D], qkv_w/b [3D, D], out_w/b [D, D], fc1_w/b [4D, D], fc2_w/b [D, 4D].
     Both streams are modulated, projected to q/k/v with their own weights, attend
     jointly over the concatenated (image first) token sequence, and then each stream
-    applies its own output projection and MLP with gated residuals."""
+    applies its own output projection and MLP with gated residuals.  With txt_pre_only (the last
+    block of a model, whose text output nothing reads) the text stream only takes part in the
+    attention and is returned unchanged."""
     xs = {'img': _f64(x_img), 'txt': _f64(x_txt)}
     temb = _f64(temb)
     mods, qkv = {}, {}
@@ -205,6 +207,9 @@ def mmdit_block(x_img, x_txt, temb, w, heads, eps=1e-6, return_parts=False):
     os_ = {'img': o[:, :Ni], 'txt': o[:, Ni:]}
     out = {}
     for s in ('img', 'txt'):
+        if s == 'txt' and txt_pre_only:
+            out[s] = xs[s]
+            continue
         _, _, g1, sh2, sc2, g2 = mods[s]
         x = xs[s] + g1[:, None, :] * linear(os_[s], w[s]['out_w'], w[s]['out_b'])
         h2 = modulate(layer_norm(x, eps), sh2, sc2)
@@ -260,15 +265,20 @@ def mmdit_final(x_img, temb, P, Hh, Ww, C, patch, eps=1e-6):
     return unpatchify(linear(y, P['f_w'], P['f_b']), Hh, Ww, C, patch)
 
 
-def mmdit_forward(latent, ctx, t, P, blocks, heads, patch):
+def mmdit_forward(latent, ctx, t, P, blocks, heads, patch, txt_pre_only_last=False):
     """One guidance-branch denoiser evaluation v = f_theta(x_t, c, t) (Sec. 4.1).
 
     latent[B, Hh, Ww, C], ctx[B, Nt, ctx_dim], t[B]; `blocks` is an iterable of per-block
-    weight dicts (may be a generator so that large models are streamed)."""
+    weight dicts (may be a generator so that large models are streamed).  txt_pre_only_last runs
+    the last block with a text stream that only supplies keys and values."""
     B, Hh, Ww, C = np.shape(latent)
     x_img, x_txt, temb = mmdit_embed(latent, ctx, t, P, patch)
-    for w in blocks:
-        x_img, x_txt = mmdit_block(x_img, x_txt, temb, w, heads)
+    it = iter(blocks)
+    w = next(it, None)
+    while w is not None:
+        nxt = next(it, None)
+        x_img, x_txt = mmdit_block(x_img, x_txt, temb, w, heads, txt_pre_only=txt_pre_only_last and nxt is None)
+        w = nxt
     return mmdit_final(x_img, temb, P, Hh, Ww, C, patch)
 
 

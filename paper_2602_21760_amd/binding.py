@@ -26,7 +26,7 @@ class HybError(RuntimeError):
 class BlockDesc(C.Structure):
     _fields_ = [("batch", C.c_int), ("n_img", C.c_int), ("n_txt", C.c_int), ("hidden", C.c_int),
                 ("heads", C.c_int), ("head_dim", C.c_int), ("mlp_ratio", C.c_int), ("dtype", C.c_int),
-                ("ln_eps", C.c_float)]
+                ("ln_eps", C.c_float), ("txt_pre_only", C.c_int)]
 
 
 class StreamWeights(C.Structure):
@@ -230,8 +230,8 @@ def hyb_linear(a, w, bias, out, epi=HYB_EPI_BIAS, residual=None, gate=None, rows
     return out
 
 
-def block_desc(batch, n_img, n_txt, hidden, heads, dtype, head_dim=64, mlp_ratio=4, ln_eps=1e-6):
-    return BlockDesc(batch, n_img, n_txt, hidden, heads, head_dim, mlp_ratio, dtype, ln_eps)
+def block_desc(batch, n_img, n_txt, hidden, heads, dtype, head_dim=64, mlp_ratio=4, ln_eps=1e-6, txt_pre_only=False):
+    return BlockDesc(batch, n_img, n_txt, hidden, heads, head_dim, mlp_ratio, dtype, ln_eps, int(txt_pre_only))
 
 
 def block_weights(img, txt):

@@ -12,6 +12,8 @@ struct AttnArgs {
     int split;
     int batch, heads, n_q, n_kv;
     float scale;     // > 0
+    int q_stride;    // query rows stored per (batch, head) in q (>= n_q); 0 means n_q.  A larger stride lets a
+                     // launch serve only the first n_q rows of a longer sequence (image-only queries over joint keys)
 };
 
 // Plain kernel (fp32 or bf16 storage, fp32 math with accurate expf).

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     const int h = pair % a.heads, b = pair / a.heads;
     const size_t bh = (size_t)b * a.heads + h;
     const int qrow = qb * BQ + wave * 32 + lq;
-    const bf16_t* qp = static_cast<const bf16_t*>(a.q) + (bh * a.n_q + min(qrow, a.n_q - 1)) * 64;
+    const bf16_t* qp = static_cast<const bf16_t*>(a.q) + (bh * (a.q_stride ? a.q_stride : a.n_q) + min(qrow, a.n_q - 1)) * 64;
     const bf16_t* kp = static_cast<const bf16_t*>(a.k) + bh * a.n_kv * 64;
     const bf16_t* vp = static_cast<const bf16_t*>(a.v) + bh * a.n_kv * 64;
 

@@ -14,7 +14,7 @@ __global__ __launch_bounds__(256) void attention_simple_kernel(AttnArgs a) {
     const int h = blockIdx.y, b = blockIdx.z;
     const bool active = row < a.n_q;
     const size_t bh = (size_t)b * a.heads + h;
-    const T* q = static_cast<const T*>(a.q) + (bh * a.n_q + (active ? row : 0)) * 64;
+    const T* q = static_cast<const T*>(a.q) + (bh * (a.q_stride ? a.q_stride : a.n_q) + (active ? row : 0)) * 64;
     const T* k = static_cast<const T*>(a.k) + bh * a.n_kv * 64;
     const T* v = static_cast<const T*>(a.v) + bh * a.n_kv * 64;
     qs[wave][lane] = to_f32<T>(q[lane]);

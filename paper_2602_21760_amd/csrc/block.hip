@@ -1,6 +1,6 @@
 // Host-side composition of one joint image+text transformer block from the library's kernels
 // (the unit of work inside the denoiser f_theta of one guidance branch, Sec. 4.1).
-// Seven launches per block: LN+modulate (both streams) -> grouped QKV GEMM with head-major
+// Seven launches per block: LN+modulate (both streams, one launch) -> grouped QKV GEMM with head-major
 // scatter -> joint attention -> grouped out-projection with gate * y + residual -> LN+modulate ->
 // grouped fc1 with GELU -> grouped fc2 with gate * y + residual.
 #include "attention.h"
@@ -76,9 +76,11 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
         HYB_CHECK_PTR(x_img_in); HYB_CHECK_PTR(x_img_out); HYB_CHECK_PTR(mod_img);
         HYB_CHECK_ALIGN(x_img_in); HYB_CHECK_ALIGN(x_img_out); HYB_CHECK_ALIGN(mod_img);
     }
+    const bool txt_pre_only = d.txt_pre_only != 0 && has_txt;   // text: keys and values only, nothing written back
     if (has_txt) {
-        HYB_CHECK_PTR(x_txt_in); HYB_CHECK_PTR(x_txt_out); HYB_CHECK_PTR(mod_txt);
-        HYB_CHECK_ALIGN(x_txt_in); HYB_CHECK_ALIGN(x_txt_out); HYB_CHECK_ALIGN(mod_txt);
+        HYB_CHECK_PTR(x_txt_in); HYB_CHECK_PTR(mod_txt);
+        HYB_CHECK_ALIGN(x_txt_in); HYB_CHECK_ALIGN(mod_txt);
+        if (!txt_pre_only) { HYB_CHECK_PTR(x_txt_out); HYB_CHECK_ALIGN(x_txt_out); }
     }
     HYB_REQUIRE(mod_stride % 4 == 0 && mod_stride >= (size_t)6 * D, HYB_ERR_SHAPE, "hyb_block_forward: mod_stride must be a multiple of 4 and at least 6 * hidden");
     const hyb_stream_weights* sw[2] = {&weights->img, &weights->txt};
@@ -86,6 +88,7 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
         if ((s == 0 && !has_img) || (s == 1 && !has_txt)) continue;
         const void* ptrs[8] = {sw[s]->w_qkv, sw[s]->w_out, sw[s]->w_fc1, sw[s]->w_fc2, sw[s]->b_qkv, sw[s]->b_out, sw[s]->b_fc1, sw[s]->b_fc2};
         for (int i = 0; i < 8; i++) {
+            if (s == 1 && txt_pre_only && i != 0 && i != 4) continue;   // only the QKV projection is used
             HYB_REQUIRE(ptrs[i] != nullptr, HYB_ERR_NULL, "hyb_block_forward: a weight pointer of the %s stream is NULL", s ? "text" : "image");
             HYB_REQUIRE(((uintptr_t)ptrs[i] & 15u) == 0, HYB_ERR_ALIGN, "hyb_block_forward: a weight pointer of the %s stream is not 16-byte aligned", s ? "text" : "image");
         }
@@ -106,11 +109,13 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     const int ntok[2] = {Ni, Nt};
     const int toff[2] = {0, Ni};
 
-    // Problems of empty streams have m = 0 and cost nothing.
-    auto group = [&](int n, int k) {
+    // Problems of empty streams have m = 0 and cost nothing.  After the attention a "pre-only" text stream
+    // is such an empty stream.
+    const int ntok_post[2] = {Ni, txt_pre_only ? 0 : Nt};
+    auto group = [&](int n, int k, const int* rows) {
         GemmGroup g = {};
         g.count = 2; g.n = n; g.k = k;
-        for (int s = 0; s < 2; s++) g.p[s].m = B * ntok[s];
+        for (int s = 0; s < 2; s++) g.p[s].m = B * rows[s];
         return g;
     };
 
@@ -122,7 +127,7 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     }
     // 2. q, k, v = h Wqkv^T + b, scattered head-major into the joint (image first) sequence
     {
-        GemmGroup g = group(3 * D, D);
+        GemmGroup g = group(3 * D, D, ntok);
         for (int s = 0; s < 2; s++) {
             GemmProblem& p = g.p[s];
             p.a = h[s]; p.w = sw[s]->w_qkv; p.bias = sw[s]->b_qkv;
@@ -133,14 +138,15 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     }
     // 3. joint attention; image rows go to o_img, text rows to o_txt
     {
-        AttnArgs a = {ws + L.q, ws + L.k, ws + L.v, o[0], o[1], Ni, B, d.heads, N, N, 0.125f};
+        AttnArgs a = {ws + L.q, ws + L.k, ws + L.v, o[0], o[1], Ni, B, d.heads, N, N, 0.125f, N};
         if (!has_img) { a.o = o[1]; a.o2 = nullptr; a.split = N; }
         if (!has_txt) { a.o2 = nullptr; a.split = N; }
+        if (txt_pre_only) { a.n_q = Ni; a.o2 = nullptr; a.split = Ni; }   // image queries only, joint keys
         if ((rc = hyb_launch_attention(a, dt, st))) return rc;
     }
     // 4. x = x + gate1 * (o Wout^T + b)
     {
-        GemmGroup g = group(D, D);
+        GemmGroup g = group(D, D, ntok_post);
         for (int s = 0; s < 2; s++) {
             GemmProblem& p = g.p[s];
             p.a = o[s]; p.w = sw[s]->w_out; p.bias = sw[s]->b_out; p.out = xout[s];
@@ -152,11 +158,11 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     {
         const float* sh[2] = {mod[0] ? mod[0] + 3 * D : nullptr, mod[1] ? mod[1] + 3 * D : nullptr};
         const float* sc[2] = {mod[0] ? mod[0] + 4 * D : nullptr, mod[1] ? mod[1] + 4 * D : nullptr};
-        if ((rc = hyb_launch_layernorm_pair(xout, sh, sc, mod_stride, h, B, ntok, D, d.ln_eps, dt, st))) return rc;
+        if ((rc = hyb_launch_layernorm_pair(xout, sh, sc, mod_stride, h, B, ntok_post, D, d.ln_eps, dt, st))) return rc;
     }
     // 6. u = GELUtanh(h2 W1^T + b1)
     {
-        GemmGroup g = group(d.mlp_ratio * D, D);
+        GemmGroup g = group(d.mlp_ratio * D, D, ntok_post);
         for (int s = 0; s < 2; s++) {
             GemmProblem& p = g.p[s];
             p.a = h[s]; p.w = sw[s]->w_fc1; p.bias = sw[s]->b_fc1; p.out = mlp[s];
@@ -165,7 +171,7 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     }
     // 7. x = x + gate2 * (u W2^T + b2)
     {
-        GemmGroup g = group(D, d.mlp_ratio * D);
+        GemmGroup g = group(D, d.mlp_ratio * D, ntok_post);
         for (int s = 0; s < 2; s++) {
             GemmProblem& p = g.p[s];
             p.a = mlp[s]; p.w = sw[s]->w_fc2; p.bias = sw[s]->b_fc2; p.out = xout[s];

@@ -20,8 +20,9 @@ def _dev(a, dtype=torch.float32):
 class MMDiT:
     """Device-resident weights + workspaces of one MMDiT-shaped denoiser (see synth.MMDiTConfig)."""
 
-    def __init__(self, cfg, globals_np, blocks_iter, batch=None):
+    def __init__(self, cfg, globals_np, blocks_iter, batch=None, txt_pre_only_last=False):
         self.cfg = cfg
+        self.txt_pre_only_last = txt_pre_only_last   # skip the dead text-stream work of the last block
         self.B = cfg.batch if batch is None else batch
         self.act = _TORCH_DT[cfg.dtype]
         self.hdt = hb.HYB_BF16 if cfg.dtype == "bf16" else hb.HYB_F32
@@ -51,6 +52,10 @@ class MMDiT:
         f32 = dict(device="cuda", dtype=torch.float32)
         act = dict(device="cuda", dtype=self.act)
         self.desc = hb.block_desc(B, cfg.n_img, cfg.n_txt, D, cfg.heads, self.hdt, cfg.head_dim, cfg.mlp_ratio, 1e-6)
+        # the same block with a text stream that only supplies keys and values (used for the last block when
+        # txt_pre_only_last is set: nothing reads the text output of the last block)
+        self.desc_pre = hb.block_desc(B, cfg.n_img, cfg.n_txt, D, cfg.heads, self.hdt, cfg.head_dim, cfg.mlp_ratio, 1e-6,
+                                      txt_pre_only=True)
         self.ws = torch.empty(max(hb.hyb_block_workspace_bytes(self.desc), 256), device="cuda", dtype=torch.uint8)
         self.t_dev = torch.empty(B, **f32)
         self.t_feat = torch.empty(B, cfg.temb_dim, **act)
@@ -96,7 +101,8 @@ class MMDiT:
         for i in range(first, last):
             mi = self.mod[:, (2 * i) * 6 * D:]
             mt = self.mod[:, (2 * i + 1) * 6 * D:]
-            hb.hyb_block_forward(self.desc, self.blocks[i], self.x_img, self.x_txt, mi, mt, self.mod_rows,
+            desc = self.desc_pre if (self.txt_pre_only_last and i == len(self.blocks) - 1) else self.desc
+            hb.hyb_block_forward(desc, self.blocks[i], self.x_img, self.x_txt, mi, mt, self.mod_rows,
                                  self.x_img, self.x_txt, self.ws)
 
     def final(self):

@@ -165,3 +165,47 @@ def test_guided_loop_with_switching_controller(hb):
     assert stages == [O.stage_of(i, tau1, tau2) for i in range(T)]
     assert [hb.hyb_switch_stage(st, i) for i in range(T)] == stages
     print("M:", g1, "tau1, tau2:", tau1, tau2, "stages:", stages)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_pre_only_text_stream_on_gpu(hb, dt):
+    """desc.txt_pre_only: image output bit-identical to the full block (a token's result does not depend on
+    which other rows share the launch), text buffer untouched (a NULL x_txt_out is accepted), and against the
+    oracle; a model whose last block runs that way returns bit-identical v."""
+    from paper_2602_21760_amd import binding as B, model
+    cfg = synth.scaled(synth.CFG1, blocks=3, hidden=256, heads=4, latent_hw=36, n_txt=77, ctx_dim=128, batch=2, dtype=dt)
+    D = cfg.hidden
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    w = synth.mmdit_block_weights(cfg, 0)
+    x_img = synth.normal(191, (cfg.batch, cfg.n_img, D), 1.0, "f32")
+    x_txt = synth.normal(192, (cfg.batch, cfg.n_txt, D), 1.0, "f32")
+    temb = synth.normal(193, (cfg.batch, D), 1.0, "f32")
+    devw = {s: {n: dev(a, tdt if n.endswith("_w") else torch.float32) for n, a in w[s].items()} for s in w}
+    mod = torch.empty(cfg.batch, 12 * D, device="cuda")
+    hb.hyb_adaln_modulation(torch.cat([devw["img"]["ada_w"], devw["txt"]["ada_w"]]).contiguous(),
+                            torch.cat([devw["img"]["ada_b"], devw["txt"]["ada_b"]]).contiguous(), dev(temb), mod)
+    hdt = B.HYB_BF16 if dt == "bf16" else B.HYB_F32
+    bw = B.block_weights(devw["img"], devw["txt"])
+    outs = {}
+    for pre in (False, True):
+        desc = B.block_desc(cfg.batch, cfg.n_img, cfg.n_txt, D, cfg.heads, hdt, txt_pre_only=pre)
+        ws = torch.empty(hb.hyb_block_workspace_bytes(desc), device="cuda", dtype=torch.uint8)
+        xi_out = torch.empty(cfg.batch, cfg.n_img, D, device="cuda")
+        xt_in = dev(x_txt)
+        xt_out = torch.full((cfg.batch, cfg.n_txt, D), 7.0, device="cuda")
+        hb.hyb_block_forward(desc, bw, dev(x_img), xt_in, mod, mod[:, 6 * D:], 12 * D, xi_out, None if pre else xt_out, ws)
+        outs[pre] = (xi_out, xt_out, xt_in)
+    assert torch.equal(outs[True][0], outs[False][0])
+    assert torch.all(outs[True][1] == 7.0) and torch.equal(outs[True][2], dev(x_txt))
+    r_img, r_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads, txt_pre_only=True)
+    assert rel_l2(host(outs[True][0]), r_img) < (TOL_BF16 if dt == "bf16" else TOL_F32)
+    # whole model
+    P = synth.mmdit_globals(cfg)
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    l2, c2 = dev(np.stack([lat, lat])), dev(np.stack([ctx_c, ctx_u]))
+    t = torch.full((2,), 0.5, device="cuda")
+    v = {}
+    for pre in (False, True):
+        m = model.MMDiT(cfg, P, synth.mmdit_blocks(cfg), txt_pre_only_last=pre)
+        v[pre] = m.forward(l2, c2, t).clone()
+    assert torch.equal(v[True], v[False])

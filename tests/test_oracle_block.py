@@ -218,3 +218,30 @@ def test_block_rows_equals_full_block():
     s_img, s_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
     np.testing.assert_allclose(s_img, f_img[:, ri], rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(s_txt, f_txt[:, rt], rtol=1e-11, atol=1e-12)
+
+
+def test_pre_only_text_stream():
+    """The last-block option: the text stream only supplies keys and values.  Pins: the image output is the
+    one of the full block (the library assembly above), the text stream comes back untouched, and a whole
+    forward -- which never reads the text output of its last block -- does not change at all."""
+    cfg = _tiny_cfg()
+    x_img, x_txt, temb, w = _block_inputs(cfg, 5, scale_w=10.0)
+    p_img, p_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads, txt_pre_only=True)
+    r_img, r_txt = _torch_block(x_img, x_txt, temb, w, cfg.heads)
+    np.testing.assert_allclose(p_img, r_img, rtol=1e-10, atol=1e-11)
+    np.testing.assert_array_equal(p_txt, x_txt)
+    assert np.abs(r_txt - x_txt).max() > 1e-3          # ... which the full block does change
+    P = {n: a * 10 for n, a in synth.mmdit_globals(cfg).items()}
+    blocks = [{s: {n: a * 10 for n, a in d.items()} for s, d in synth.mmdit_block_weights(cfg, i).items()}
+              for i in range(3)]
+    lat, ctx_c, _ = synth.mmdit_inputs(cfg)
+    t = np.array([0.5])
+    v_full = O.mmdit_forward(lat[None], ctx_c[None], t, P, blocks, cfg.heads, cfg.patch)
+    v_pre = O.mmdit_forward(lat[None], ctx_c[None], t, P, iter(blocks), cfg.heads, cfg.patch, txt_pre_only_last=True)
+    np.testing.assert_array_equal(v_pre, v_full)
+    # the flag reaches the LAST block only: with it on every block the result would differ
+    x_i, x_t, temb_f = O.mmdit_embed(lat[None], ctx_c[None], t, P, cfg.patch)
+    for wb in blocks:
+        x_i, x_t = O.mmdit_block(x_i, x_t, temb_f, wb, cfg.heads, txt_pre_only=True)
+    v_all = O.mmdit_final(x_i, temb_f, P, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch)
+    assert np.abs(v_all - v_full).max() > 1e-8
