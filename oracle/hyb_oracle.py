@@ -250,11 +250,15 @@ def mmdit_block_rows(x_img, x_txt, temb, w, heads, img_rows, txt_rows, eps=1e-6)
     return out['img'], out['txt']
 
 
-def mmdit_embed(latent, ctx, t, P, patch):
-    """Token / context / timestep embeddings of the branch forward."""
+def mmdit_embed(latent, ctx, t, P, patch, pooled=None):
+    """Token / context / timestep embeddings of the branch forward.  With a pooled text vector
+    pooled[B, pooled_dim], its projection W_p2 SiLU(W_p1 pooled + b_p1) + b_p2 is added to the
+    timestep embedding, so that the modulation of every block also depends on the prompt."""
     x_img = linear(patchify(latent, patch), P['pe_w'], P['pe_b']) + _f64(P['pos'])[None]
     x_txt = linear(ctx, P['ce_w'], P['ce_b'])
     temb = timestep_mlp(t, P['t1_w'], P['t1_b'], P['t2_w'], P['t2_b'], P['t1_w'].shape[1])
+    if pooled is not None:
+        temb = temb + linear(silu(linear(pooled, P['p1_w'], P['p1_b'])), P['p2_w'], P['p2_b'])
     return x_img, x_txt, temb
 
 
@@ -265,14 +269,15 @@ def mmdit_final(x_img, temb, P, Hh, Ww, C, patch, eps=1e-6):
     return unpatchify(linear(y, P['f_w'], P['f_b']), Hh, Ww, C, patch)
 
 
-def mmdit_forward(latent, ctx, t, P, blocks, heads, patch, txt_pre_only_last=False):
+def mmdit_forward(latent, ctx, t, P, blocks, heads, patch, txt_pre_only_last=False, pooled=None):
     """One guidance-branch denoiser evaluation v = f_theta(x_t, c, t) (Sec. 4.1).
 
     latent[B, Hh, Ww, C], ctx[B, Nt, ctx_dim], t[B]; `blocks` is an iterable of per-block
     weight dicts (may be a generator so that large models are streamed).  txt_pre_only_last runs
-    the last block with a text stream that only supplies keys and values."""
+    the last block with a text stream that only supplies keys and values; pooled[B, pooled_dim]
+    is the optional pooled text vector (see mmdit_embed)."""
     B, Hh, Ww, C = np.shape(latent)
-    x_img, x_txt, temb = mmdit_embed(latent, ctx, t, P, patch)
+    x_img, x_txt, temb = mmdit_embed(latent, ctx, t, P, patch, pooled)
     it = iter(blocks)
     w = next(it, None)
     while w is not None:

@@ -61,6 +61,9 @@ class MMDiT:
         self.t_feat = torch.empty(B, cfg.temb_dim, **act)
         self.t_hid = torch.empty(B, D, **act)
         self.temb = torch.empty(B, D, **f32)
+        if cfg.pooled_dim:
+            self.pooled_act = torch.empty(B, cfg.pooled_dim, **act)
+            self.p_hid = torch.empty(B, D, **act)
         self.mod = torch.empty(B, self.mod_rows, **f32)
         self.tok = torch.empty(B, cfg.n_img, cfg.patch_dim, **act)
         self.ctx_act = torch.empty(B, cfg.n_txt, cfg.ctx_dim, **act)
@@ -81,12 +84,17 @@ class MMDiT:
         assert self.pos.shape[0] == cfg.n_img
         self._alloc()
 
-    def embed(self, latent, ctx, t):
-        """latent: f32[B, Hh, Ww, C]; ctx: f32[B, Nt, ctx_dim]; t: f32[B] (device tensors)."""
+    def embed(self, latent, ctx, t, pooled=None):
+        """latent: f32[B, Hh, Ww, C]; ctx: f32[B, Nt, ctx_dim]; t: f32[B]; pooled: f32[B, pooled_dim] when the
+        configuration has a pooled text vector (device tensors)."""
         cfg, g = self.cfg, self.g
         hb.hyb_timestep_embedding(t, self.t_feat)
         hb.hyb_linear(self.t_feat, g["t1_w"], g["t1_b"], self.t_hid, hb.HYB_EPI_SILU)
         hb.hyb_linear(self.t_hid, g["t2_w"], g["t2_b"], self.temb, hb.HYB_EPI_BIAS)
+        if cfg.pooled_dim:   # temb += W_p2 SiLU(W_p1 pooled + b_p1) + b_p2 (the sum is the residual epilogue)
+            hb.hyb_convert(pooled, self.pooled_act)
+            hb.hyb_linear(self.pooled_act, g["p1_w"], g["p1_b"], self.p_hid, hb.HYB_EPI_SILU)
+            hb.hyb_linear(self.p_hid, g["p2_w"], g["p2_b"], self.temb, hb.HYB_EPI_GATE_RESIDUAL, residual=self.temb)
         hb.hyb_adaln_modulation(self.ada_w, self.ada_b, self.temb, self.mod)
         hb.hyb_patchify(latent, self.tok, cfg.patch)
         for b in range(self.B):    # the positional table is the "residual" of the patch projection
@@ -113,9 +121,9 @@ class MMDiT:
         hb.hyb_unpatchify(self.out_tok, self.v, cfg.patch)
         return self.v
 
-    def forward(self, latent, ctx, t):
+    def forward(self, latent, ctx, t, pooled=None):
         """One denoiser evaluation for every batch row; returns v[B, Hh, Ww, C] (activation dtype)."""
-        self.embed(latent, ctx, t)
+        self.embed(latent, ctx, t, pooled)
         self.run_blocks()
         return self.final()
 

@@ -41,6 +41,7 @@ class MMDiTConfig:
     steps: int = 1
     shift: float = 3.0
     guidance: float = 7.0
+    pooled_dim: int = 0   # > 0: a pooled text vector of this width also conditions the modulation
 
     @property
     def n_img(self):
@@ -133,6 +134,8 @@ def mmdit_globals(cfg):
               ("t1_w", (D, cfg.temb_dim)), ("t1_b", (D,)), ("t2_w", (D, D)), ("t2_b", (D,)),
               ("f_ada_w", (2 * D, D)), ("f_ada_b", (2 * D,)), ("f_w", (cfg.patch_dim, D)),
               ("f_b", (cfg.patch_dim,))]
+    if cfg.pooled_dim:   # tensor indices 12..15
+        shapes += [("p1_w", (D, cfg.pooled_dim)), ("p1_b", (D,)), ("p2_w", (D, D)), ("p2_b", (D,))]
     P = {n: normal(1000 + i, s, 0.02, dt) for i, (n, s) in enumerate(shapes)}
     P["pos"] = normal(4, (cfg.n_img, D), 0.02, dt)
     return P
@@ -165,6 +168,11 @@ def mmdit_inputs(cfg):
     ctx_c = normal(2, (cfg.n_txt, cfg.ctx_dim), 1.0, cfg.dtype)
     ctx_u = normal(3, (cfg.n_txt, cfg.ctx_dim), 1.0, cfg.dtype)
     return lat, ctx_c, ctx_u
+
+
+def mmdit_pooled(cfg):
+    """Pooled text vectors [pooled_dim] of the conditional / unconditional prompt (seeds 5, 6)."""
+    return normal(5, (cfg.pooled_dim,), 1.0, cfg.dtype), normal(6, (cfg.pooled_dim,), 1.0, cfg.dtype)
 
 
 _SDXL_TENSORS = ("gn_g", "gn_b", "ln1_g", "ln1_b", "q1_w", "k1_w", "v1_w", "o1_w", "o1_b",

@@ -209,3 +209,22 @@ def test_pre_only_text_stream_on_gpu(hb, dt):
         m = model.MMDiT(cfg, P, synth.mmdit_blocks(cfg), txt_pre_only_last=pre)
         v[pre] = m.forward(l2, c2, t).clone()
     assert torch.equal(v[True], v[False])
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_forward_with_pooled_text_conditioning(hb, dt):
+    """A reduced model with a pooled text vector per branch (conditional / unconditional), both branches in
+    one batch, against the oracle."""
+    from paper_2602_21760_amd import model
+    cfg = synth.scaled(synth.CFG1, blocks=2, hidden=256, heads=4, latent_hw=20, n_txt=21, ctx_dim=128, batch=2, dtype=dt,
+                       pooled_dim=96)
+    P = synth.mmdit_globals(cfg)
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    pc, pu = synth.mmdit_pooled(cfg)
+    latent, ctx, pooled = np.stack([lat, lat]), np.stack([ctx_c, ctx_u]), np.stack([pc, pu])
+    m = model.MMDiT(cfg, P, synth.mmdit_blocks(cfg))
+    v = m.forward(dev(latent), dev(ctx), torch.full((2,), 0.5, device="cuda"), dev(pooled))
+    ref = O.mmdit_forward(latent, ctx, np.array([0.5, 0.5]), P, synth.mmdit_blocks(cfg), cfg.heads, cfg.patch, pooled=pooled)
+    assert rel_l2(host(v), ref) < (TOL_BF16 if dt == "bf16" else TOL_F32)
+    ref0 = O.mmdit_forward(latent, ctx, np.array([0.5, 0.5]), P, synth.mmdit_blocks(cfg), cfg.heads, cfg.patch)
+    assert rel_l2(ref, ref0) > 10 * (TOL_BF16 if dt == "bf16" else TOL_F32) or dt == "bf16"   # the pooled path matters

@@ -245,3 +245,27 @@ def test_pre_only_text_stream():
         x_i, x_t = O.mmdit_block(x_i, x_t, temb_f, wb, cfg.heads, txt_pre_only=True)
     v_all = O.mmdit_final(x_i, temb_f, P, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch)
     assert np.abs(v_all - v_full).max() > 1e-8
+
+
+def test_pooled_text_conditioning():
+    """Optional pooled text vector: its two-layer projection is added to the timestep embedding.  Pinned to a
+    torch library assembly, to the un-pooled embedding when the second projection is zero, and through the
+    forward (the prediction reacts to the pooled vector)."""
+    cfg = _tiny_cfg(pooled_dim=48)
+    P = {n: a * 10 for n, a in synth.mmdit_globals(cfg).items()}
+    lat, ctx_c, _ = synth.mmdit_inputs(cfg)
+    pc, pu = synth.mmdit_pooled(cfg)
+    t = np.array([0.5])
+    x_i, x_t, temb = O.mmdit_embed(lat[None], ctx_c[None], t, P, cfg.patch, pooled=pc[None])
+    x_i0, x_t0, temb0 = O.mmdit_embed(lat[None], ctx_c[None], t, P, cfg.patch)
+    ref = T(temb0) + F.linear(F.silu(F.linear(T(pc[None]), T(P["p1_w"]), T(P["p1_b"]))), T(P["p2_w"]), T(P["p2_b"]))
+    np.testing.assert_allclose(temb, ref.numpy(), rtol=1e-12)
+    np.testing.assert_array_equal(x_i, x_i0)
+    np.testing.assert_array_equal(x_t, x_t0)
+    assert np.abs(temb - temb0).max() > 1e-3
+    Pz = dict(P, p2_w=np.zeros_like(P["p2_w"]), p2_b=np.zeros_like(P["p2_b"]))
+    np.testing.assert_array_equal(O.mmdit_embed(lat[None], ctx_c[None], t, Pz, cfg.patch, pooled=pc[None])[2], temb0)
+    blocks = [{s: {n: a * 10 for n, a in d.items()} for s, d in synth.mmdit_block_weights(cfg, i).items()} for i in range(2)]
+    v_c = O.mmdit_forward(lat[None], ctx_c[None], t, P, blocks, cfg.heads, cfg.patch, pooled=pc[None])
+    v_u = O.mmdit_forward(lat[None], ctx_c[None], t, P, blocks, cfg.heads, cfg.patch, pooled=pu[None])
+    assert np.abs(v_c - v_u).max() > 1e-8
