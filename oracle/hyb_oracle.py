@@ -313,6 +313,30 @@ def sdxl_block(x, ctx, w, heads):
     return x + c
 
 
+def sdxl_block_rows(x, ctx, w, heads, rows):
+    """The same block for the listed token rows only (sampled outputs at sizes where the full block is
+    too slow): the group statistics, and the self-attention keys and values, are formed from ALL tokens;
+    queries and everything after the self-attention only for the selected rows (cross-attention keys come
+    from the context, the rest is per token).  Returns out[B, len(rows), C]."""
+    x = _f64(x)
+    rows = np.asarray(rows, dtype=np.int64)
+    g = group_norm(x, 32, w['gn_g'], w['gn_b'], 1e-5)
+    h = layer_norm_affine(g, w['ln1_g'], w['ln1_b'])
+    k = split_heads(linear(h, w['k1_w']), heads)
+    v = split_heads(linear(h, w['v1_w']), heads)
+    q = split_heads(linear(h[:, rows], w['q1_w']), heads)
+    a = g[:, rows] + linear(attention(q, k, v), w['o1_w'], w['o1_b'])
+    h = layer_norm_affine(a, w['ln2_g'], w['ln2_b'])
+    q = split_heads(linear(h, w['q2_w']), heads)
+    k = split_heads(linear(ctx, w['k2_w']), heads)
+    v = split_heads(linear(ctx, w['v2_w']), heads)
+    b = a + linear(attention(q, k, v), w['o2_w'], w['o2_b'])
+    h = layer_norm_affine(b, w['ln3_g'], w['ln3_b'])
+    u, gate = np.split(linear(h, w['ff1_w'], w['ff1_b']), 2, axis=-1)
+    c = b + linear(u * gelu_erf(gate), w['ff2_w'], w['ff2_b'])
+    return x[:, rows] + c
+
+
 # --------------------------------------------------------------------------------------
 # Guidance, discrepancy, scheduler (the parts the paper states explicitly)
 # --------------------------------------------------------------------------------------

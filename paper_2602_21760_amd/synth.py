@@ -96,6 +96,9 @@ CFG6 = MMDiTConfig("cfg6_sd3_2560_bf16", blocks=24, hidden=1536, heads=24, laten
                    latent_c=16, n_txt=333, ctx_dim=4096, batch=1, dtype="bf16")
 CFG5A = SDXLStageConfig("cfg5_sdxl_stageA", blocks=10, tokens=4096, channels=640, heads=10)
 CFG5B = SDXLStageConfig("cfg5_sdxl_stageB", blocks=20, tokens=1024, channels=1280, heads=20)
+# the same two stages at 2048 x 2048 (4 x the tokens)
+CFG7A = SDXLStageConfig("sdxl_2048_stageA", blocks=10, tokens=16384, channels=640, heads=10)
+CFG7B = SDXLStageConfig("sdxl_2048_stageB", blocks=20, tokens=4096, channels=1280, heads=20)
 CFG5_LATENT = (128, 128, 4)
 CFG5_GUIDANCE = 5.0
 

@@ -80,6 +80,25 @@ def test_sdxl_stage_real_shapes_one_block(hb, stage):
     assert rel_l2(got - x, ref - x) < 5e-2
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("stage", ["A", "B"])
+def test_sdxl_stage_2048_shapes_sampled_rows(hb, stage):
+    """One block at the stage shapes of a 2048 x 2048 image (16384 tokens x 640, 4096 x 1280; batch 2) on
+    sampled token rows."""
+    from paper_2602_21760_amd import model
+    cfg = synth.CFG7A if stage == "A" else synth.CFG7B
+    w = synth.sdxl_block_weights(cfg, 0)
+    x, ctx = synth.sdxl_inputs(cfg)
+    st = model.SDXLStage(cfg, [w])
+    dx = dev(x)
+    st.forward(dx, dev(ctx))
+    rows = np.unique(np.concatenate([[0, 127, 128, cfg.tokens - 1], np.random.default_rng(6).integers(0, cfg.tokens, 44)]))
+    ref = O.sdxl_block_rows(x, ctx, w, cfg.heads, rows)
+    got = host(dx)[:, rows]
+    assert rel_l2(got, ref) < TOL_BF16
+    assert rel_l2(got - x[:, rows], ref - x[:, rows]) < 5e-2
+
+
 def test_sdxl_guidance_step(hb):
     """CFG (scale 5), both discrepancies and the Euler-epsilon update on the 128 x 128 x 4 latent; the two
     branch predictions are seeded stand-ins of the latent's shape."""

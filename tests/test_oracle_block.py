@@ -269,3 +269,12 @@ def test_pooled_text_conditioning():
     v_c = O.mmdit_forward(lat[None], ctx_c[None], t, P, blocks, cfg.heads, cfg.patch, pooled=pc[None])
     v_u = O.mmdit_forward(lat[None], ctx_c[None], t, P, blocks, cfg.heads, cfg.patch, pooled=pu[None])
     assert np.abs(v_c - v_u).max() > 1e-8
+
+
+def test_sdxl_block_rows_equals_full_block():
+    cfg = synth.SDXLStageConfig("t", blocks=1, tokens=23, channels=128, heads=2, n_ctx=7, ctx_dim=48, batch=2, dtype="f32")
+    w = {n: (a * 8 if n.endswith("_w") else a) for n, a in synth.sdxl_block_weights(cfg, 0).items()}
+    x, ctx = synth.sdxl_inputs(cfg)
+    rows = [0, 22, 5, 11]
+    np.testing.assert_allclose(O.sdxl_block_rows(x, ctx, w, cfg.heads, rows), O.sdxl_block(x, ctx, w, cfg.heads)[:, rows],
+                               rtol=1e-11, atol=1e-12)
