@@ -21,7 +21,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch from the rocprofv3 PMC runs recorded in profiles/pmc_hbm_traffic_cfg2_kernels.md
 # (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain 1 GiB copy gives on this counter set)
-TRAFFIC_BYTES = {"attention_mfma": 256.4e6, "guidance_pass": 806.1e6,
+TRAFFIC_BYTES = {"attention_mfma": 54.5e6, "guidance_pass": 806.1e6,
                  "gemm_mfma_128x128.epi4.n4608.k1536": 252.3e6, "gemm_mfma_128x128.epi1.n6144.k1536": 249.0e6,
                  "gemm_mfma_128x128.epi3.n1536.k6144": 577.0e6}
 
