@@ -13,7 +13,9 @@
 // with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 16 consecutive rows hit distinct
 // banks (the swizzle is applied on the global side: each lane picks which 16 bytes it fetches).
 // Waits on the copies are explicit (s_waitcnt vmcnt + s_barrier); a full __syncthreads() would
-// force vmcnt(0) on every barrier through its fence.
+// force vmcnt(0) on every barrier through its fence.  The fragments of the four k-steps of a slab
+// live in a ring of four register sets and are read two k-steps ahead of the MFMAs that use them,
+// also across the slab boundary, which leaves a single barrier per slab (before k-step 2).
 //
 // Epilogue: the accumulators (+ bias, activation, gate) are staged through LDS (reusing the slab
 // buffers) and written out row-contiguously, 16 bytes per lane, so that global stores and the
@@ -26,6 +28,8 @@
 // reduction order over k is fixed and a token's result does not depend on its tile row, so
 // results are deterministic and batch-invariant.
 #include "gemm.h"
+
+#include <type_traits>
 
 namespace {
 
@@ -92,35 +96,69 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[fn][tm][i] = 0.f;
 
+    // Fragment addresses inside a stage.  With the XOR swizzle the 16-byte slot of the read for k-step kk of
+    // MFMA tile t is (lane part) ^ 2 (kk ^ 2 t), so four per-lane bases per operand cover all sixteen reads of
+    // a slab and the tile row block (t * 32 rows) is an immediate offset.
+    const int lb = (hi ^ lr ^ (lr >> 3)) & 7;
+    int a_base[4], w_base[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) {
+        a_base[c] = (wt * 64 + lr) * ROWB + ((lb ^ (2 * c)) * 16);
+        w_base[c] = BM * ROWB + (wf * 64 + lr) * ROWB + ((lb ^ (2 * c)) * 16);
+    }
+    // Ring of four fragment sets, one per k-step of a slab; the reads run two k-steps (8 MFMAs) ahead of their
+    // use, across the slab boundary.
+    bf16x8 af[4][2], wfr[4][2];
+    auto read_set = [&](int stage, int kk) {
+        const unsigned char* base = smem + stage * STAGE_BYTES;
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+            af[kk][t] = *reinterpret_cast<const bf16x8*>(base + a_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+            wfr[kk][t] = *reinterpret_cast<const bf16x8*>(base + w_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+        }
+    };
+
+    // Main loop.  Slab s sits in stage s % 2.  ONE barrier per slab, before k-step 2: by then every wave has
+    // issued (and, after the lgkmcnt wait, completed) all its reads of slab s, so stage s % 2 can be refilled with
+    // slab s + 2 right behind the barrier, and the copy of slab s + 1 (issued one slab earlier) is awaited just
+    // before it, so that k-steps 2 and 3 can already fetch the first fragments of slab s + 1.
     const int nslab = k / BK;
     issue(0, 0);
-    for (int s = 0; s < nslab; s++) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of slab s has landed
-        __builtin_amdgcn_s_barrier();                      // ... and everyone else's; stage (s+1)%2 is free
-        if (s + 1 < nslab) issue(s + 1, (s + 1) & 1);
-        const unsigned char* sa = smem + (s & 1) * STAGE_BYTES;
-        const unsigned char* sw = sa + BM * ROWB;
-        bf16x8 af[2][2], wfr[2][2];   // [kk parity][tile]
-        auto read_frags = [&](int kk, bf16x8* a2, bf16x8* w2) {
-#pragma unroll
-            for (int t = 0; t < 2; t++) {
-                const int ra = wt * 64 + t * 32 + lr, rw = wf * 64 + t * 32 + lr;
-                a2[t] = *reinterpret_cast<const bf16x8*>(sa + ra * ROWB + (((kk * 2 + hi) ^ swz(ra)) * 16));
-                w2[t] = *reinterpret_cast<const bf16x8*>(sw + rw * ROWB + (((kk * 2 + hi) ^ swz(rw + BM)) * 16));
-            }
-        };
-        read_frags(0, af[0], wfr[0]);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (nslab > 1) issue(1, 1);
+    read_set(0, 0);
+    read_set(0, 1);
+    auto slab_step = [&](int s, auto stage_tag) {
+        constexpr int STG = decltype(stage_tag)::value;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
-            if (kk + 1 < BK / 16) read_frags(kk + 1, af[(kk + 1) & 1], wfr[(kk + 1) & 1]);
+            if (kk == 2 && s + 1 < nslab) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's share of slab s + 1 has landed
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and its reads of slab s are complete
+                __builtin_amdgcn_s_barrier();
+                if (s + 2 < nslab) issue(s + 2, STG);
+            }
+            if (kk < 2) read_set(STG, kk + 2);
+            else if (s + 1 < nslab) read_set(STG ^ 1, kk - 2);
 #pragma unroll
             for (int fn = 0; fn < 2; fn++)
 #pragma unroll
                 for (int tm = 0; tm < 2; tm++)
-                    acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[kk & 1][fn], af[kk & 1][tm], acc[fn][tm], 0, 0, 0);
+                    acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[kk][fn], af[kk][tm], acc[fn][tm], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; j++) {   // one fragment read between two MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
         }
-        __builtin_amdgcn_s_barrier();                      // everyone is done reading stage s%2
+    };
+    for (int s = 0; s < nslab; s += 2) {
+        slab_step(s, std::integral_constant<int, 0>{});
+        if (s + 1 < nslab) slab_step(s + 1, std::integral_constant<int, 1>{});
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();                          // every wave is done with the slab buffers
 
     // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
     // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*64 + tm*32 + lr.
