@@ -101,7 +101,8 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     // [buffer][K tile | V tile]
     __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * TILE_BYTES];
 
-    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // uniform: LDS copy targets (M0) become scalar arithmetic
     const int lq = lane % 32, g = lane / 32;
     // Workgroups go round-robin to the 8 XCDs (each with its own L2) in launch order.  When the number of
     // (batch, head) pairs is a multiple of 8, pair p is served entirely by XCD p % 8, so its K and V stay in

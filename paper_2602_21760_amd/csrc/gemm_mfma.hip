@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     const bf16_t* A = static_cast<const bf16_t*>(p.a);
     const bf16_t* W = static_cast<const bf16_t*>(p.w);
 
-    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int tid = threadIdx.x, lane = tid % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // uniform: LDS copy targets (M0) become scalar arithmetic
     const int wt = wave % 2, wf = wave / 2;          // wave position: tokens, features
     const int lr = lane % 32, hi = lane / 32;
 
