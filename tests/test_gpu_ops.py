@@ -144,3 +144,28 @@ def test_attention_invariants_on_gpu(hb, dt):
     got = host(o)
     assert np.isfinite(got).all()
     assert rel_l2(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 2e-2)
+
+
+@pytest.mark.parametrize("growth", [3.0, 7.5, 40.0])
+def test_attention_running_maximum_schedules(hb, growth):
+    """Scores that rise steadily along the key axis: the row maximum of every 64-key tile exceeds the previous
+    one by `growth` (in base-2 exponent units), so the kernel's deferred rescaling (it only advances its running
+    maximum when the tile maximum has grown by more than 2^8) sees growth below, just below and far above its
+    threshold; descending order (the first tile holds the maximum) rides along as the second head."""
+    B, H, N = 1, 2, 650                               # 10 full tiles + a ragged one
+    rng = np.random.default_rng(77)
+    q = np.zeros((B, H, N, 64), np.float32)
+    k = np.zeros((B, H, N, 64), np.float32)
+    q[..., 0] = 8.0
+    ramp = growth / 64.0 * np.arange(N) / (8.0 * 0.125 * 1.4426950408889634)    # score_j * log2(e) = growth * j / 64
+    k[0, 0, :, 0] = ramp
+    k[0, 1, :, 0] = ramp[::-1]
+    q[..., 1:] = synth.round_bf16(0.05 * rng.standard_normal((B, H, N, 63)).astype(np.float32))
+    k[..., 1:] = synth.round_bf16(0.05 * rng.standard_normal((B, H, N, 63)).astype(np.float32))
+    k = synth.round_bf16(k)
+    v = _data(78, (B, H, N, 64), "bf16")
+    o = torch.empty(B, N, H * 64, device="cuda", dtype=torch.bfloat16)
+    hb.hyb_joint_attention(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), o)
+    got = host(o)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, O.attention(q, k, v)) < 1e-2
