@@ -82,4 +82,16 @@ __device__ __forceinline__ float gelu_tanh_f(float z) {
     const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
     return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
 }
-__device__ __forceinline__ float gelu_erf_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.7071067811865476f)); }
+// Exact-erf GELU with erf from the rational approximation 7.1.26 of Abramowitz & Stegun,
+// erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0 (absolute error < 1.5e-7, far inside
+// the fp32 tolerance of the workloads), a dozen instructions instead of the library routine's branches.
+__device__ __forceinline__ float gelu_erf_f(float z) {
+    const float x = fabsf(z) * 0.7071067811865476f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float poly = fmaf(1.061405429f, t, -1.453152027f);
+    poly = fmaf(poly, t, 1.421413741f);
+    poly = fmaf(poly, t, -0.284496736f);
+    poly = fmaf(poly, t, 0.254829592f);
+    const float erf_abs = 1.0f - poly * t * __expf(-x * x);
+    return 0.5f * z * (1.0f + copysignf(erf_abs, z));
+}
