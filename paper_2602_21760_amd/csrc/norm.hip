@@ -162,12 +162,12 @@ __global__ __launch_bounds__(256) void adaln_kernel(const WT* __restrict__ w, co
 
 // ------------------------------------------------------------------------------------------
 // GroupNorm on token-major data x[B, T, C], groups of C/G consecutive channels, statistics over
-// (T, C/G) per sample.  Two kernels, both with one thread per 4-channel vector (so every load and
+// (T, C/G) per sample.  Three kernels; 1 and 3 use one thread per 4-channel vector (so every load and
 // store is a coalesced 16-byte access and a thread stays inside one group):
 //  1. each workgroup sums x and x^2 over its chunk of tokens (fp32 per thread, then the threads of a
 //     group are added in a fixed order in fp64) -> partial[b][chunk][group][2];
-//  2. each workgroup adds the partials of a sample in chunk order (fp64), forms mean and 1/std, and
-//     normalises its chunk: y = (x - mean) rstd gamma + beta.
+//  2. one workgroup per sample adds the partials in chunk order (fp64) and forms mean and 1/std per group;
+//  3. each workgroup normalises its chunk: y = (x - mean) rstd gamma + beta.
 // No atomics: the result is deterministic and independent of the batch index.
 // ------------------------------------------------------------------------------------------
 constexpr int kGnChunks = 128;
@@ -201,23 +201,33 @@ __global__ void groupnorm_stats_kernel(const float* __restrict__ x, double* __re
     }
 }
 
-__global__ void groupnorm_apply_kernel(const float* __restrict__ x, const double* __restrict__ partial,
+// One workgroup per sample, one thread per group: adds the chunk partials in chunk order (fp64) and leaves
+// (mean, 1/std) as two floats per group.
+__global__ void groupnorm_finalize_kernel(const double* __restrict__ partial, float* __restrict__ stats, int nchunks,
+                                          int groups, double count, float eps) {
+    const int g = threadIdx.x, b = blockIdx.x;
+    if (g >= groups) return;
+    const double* p = partial + ((size_t)b * nchunks * groups + g) * 2;
+    double ds = 0.0, dq = 0.0;
+#pragma unroll 8
+    for (int c = 0; c < nchunks; c++) {
+        ds += p[(size_t)c * groups * 2];
+        dq += p[(size_t)c * groups * 2 + 1];
+    }
+    const double mean_d = ds / count;
+    const double var_d = fmax(dq / count - mean_d * mean_d, 0.0);
+    stats[((size_t)b * groups + g) * 2] = (float)mean_d;
+    stats[((size_t)b * groups + g) * 2 + 1] = (float)(1.0 / sqrt(var_d + (double)eps));
+}
+
+__global__ void groupnorm_apply_kernel(const float* __restrict__ x, const float* __restrict__ stats,
                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                        float* __restrict__ out, int tokens, int channels, int groups,
-                                       int tokens_per_chunk, float eps) {
+                                       int tokens_per_chunk) {
     const int nvec = channels / 4, vec = threadIdx.x;
-    const int chunk = blockIdx.x, b = blockIdx.y, nchunks = gridDim.x;
+    const int chunk = blockIdx.x, b = blockIdx.y;
     const int grp = vec / (nvec / groups);
-    double ds = 0.0, dq = 0.0;
-    for (int c = 0; c < nchunks; c++) {
-        const double* p = partial + (((size_t)b * nchunks + c) * groups + grp) * 2;
-        ds += p[0];
-        dq += p[1];
-    }
-    const double cnt = (double)tokens * (channels / groups);
-    const double mean_d = ds / cnt;
-    const double var_d = fmax(dq / cnt - mean_d * mean_d, 0.0);
-    const float mean = (float)mean_d, rstd = (float)(1.0 / sqrt(var_d + (double)eps));
+    const float mean = stats[((size_t)b * groups + grp) * 2], rstd = stats[((size_t)b * groups + grp) * 2 + 1];
     const f32x4 gm = reinterpret_cast<const f32x4*>(gamma)[vec], bt = reinterpret_cast<const f32x4*>(beta)[vec];
     const f32x4* xb = reinterpret_cast<const f32x4*>(x + (size_t)b * tokens * channels);
     f32x4* ob = reinterpret_cast<f32x4*>(out + (size_t)b * tokens * channels);
@@ -316,8 +326,12 @@ int hyb_launch_layernorm_pair(const float* const x[2], const float* const shift[
     return launch_layernorm(a, blocks[0] + blocks[1], (double)batch * (tokens[0] + tokens[1]), out_dtype, false, st);
 }
 
-size_t hyb_groupnorm_scratch_bytes(int batch, int groups) {
+// chunk partials (fp64 sum and sum of squares), then (mean, 1/std) per (sample, group)
+static size_t gn_partial_bytes(int batch, int groups) {
     return hyb_align_up((size_t)batch * kGnChunks * groups * 2 * sizeof(double), 256);
+}
+size_t hyb_groupnorm_scratch_bytes(int batch, int groups) {
+    return gn_partial_bytes(batch, groups) + hyb_align_up((size_t)batch * groups * 2 * sizeof(float), 256);
 }
 
 // channels % (4 * groups) == 0 and channels <= 4096 (one thread per 4-channel vector, <= 1024 threads).
@@ -333,7 +347,10 @@ int hyb_launch_groupnorm(const float* x, const float* gamma, const float* beta, 
     dim3 grid(used, batch), block(nvec);
     HybTraceScope trace("groupnorm", "byte", (double)batch * tokens * channels * 12, st);
     hipLaunchKernelGGL(groupnorm_stats_kernel, grid, block, nvec * 2 * sizeof(float), st, x, (double*)scratch, tokens, channels, groups, tpc);
-    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, block, 0, st, x, (const double*)scratch, gamma, beta, out, tokens, channels, groups, tpc, eps);
+    float* stats = reinterpret_cast<float*>(static_cast<char*>(scratch) + gn_partial_bytes(batch, groups));
+    hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(batch), dim3(64 * ((groups + 63) / 64)), 0, st, (const double*)scratch, stats, used, groups,
+                       (double)tokens * (channels / groups), eps);
+    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, block, 0, st, x, (const float*)stats, gamma, beta, out, tokens, channels, groups, tpc);
     return hyb_check_launch("groupnorm");
 }
 
