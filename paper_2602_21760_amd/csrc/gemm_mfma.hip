@@ -2,7 +2,7 @@
 // W [n, k] features-out x features-in, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
 //
 // Tiling: a workgroup of 4 waves (2 x 2) owns a 128 x 128 output tile; each wave owns 2 x 2 MFMA
-// tiles of 32 x 32.  The weight fragment is the MFMA "A" operand and the token fragment the "B"
+// tiles of 32 x 32 (small problems: 64 x 128 tiles, 1 x 2 MFMA tiles per wave, see launch_epi).  The weight fragment is the MFMA "A" operand and the token fragment the "B"
 // operand, so the 16 accumulator registers of a lane run along the output-feature axis (4
 // consecutive features per group of 4 registers, one token per lane).
 //
@@ -33,11 +33,16 @@
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 64;
+constexpr int BN = 128, BK = 64;
 constexpr int ROWB = BK * 2;                    // bytes per LDS row of a slab
-constexpr int STAGE_BYTES = (BM + BN) * ROWB;   // 32 KB
-constexpr int CPW = STAGE_BYTES / 1024 / 4;     // 1 KB chunks per wave per slab (8)
-constexpr int SMEM_BYTES = 2 * STAGE_BYTES;     // 64 KB -> two workgroups per CU
+// The tile height is 64 TMW tokens (TMW = MFMA token tiles per wave): 128 for the large GEMMs, 64 for
+// launches that would otherwise leave most of the chip idle (fewer than three quarters of a wave of tiles).
+template <int TMW> struct Geo {
+    static constexpr int BM = 64 * TMW;
+    static constexpr int STAGE_BYTES = (BM + BN) * ROWB;   // 32 KB / 24 KB
+    static constexpr int CPW = STAGE_BYTES / 1024 / 4;     // 1 KB chunks per wave per slab (8 / 6)
+    static constexpr int SMEM_BYTES = 2 * STAGE_BYTES;     // 64 KB -> two workgroups per CU / 48 KB -> three
+};
 constexpr int OUT_STRIDE_B16 = BN * 2 + 16;     // staging row strides (bytes), padded against conflicts
 constexpr int OUT_STRIDE_F32 = BN * 4 + 16;
 
@@ -50,9 +55,10 @@ __device__ __forceinline__ void load_lds16(const void* g, void* l) {
     __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
 }
 
-template <typename OT, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+template <typename OT, int EPI, int TMW>
+__global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
+    constexpr int BM = Geo<TMW>::BM, STAGE_BYTES = Geo<TMW>::STAGE_BYTES, CPW = Geo<TMW>::CPW;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[Geo<TMW>::SMEM_BYTES];
 
     int tile = blockIdx.x;
     const int pi = tile >= tiles0 ? 1 : 0;
@@ -70,7 +76,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     const int wt = wave % 2, wf = wave / 2;          // wave position: tokens, features
     const int lr = lane % 32, hi = lane / 32;
 
-    // This wave's 8 chunks of a slab: chunk c covers stage rows 8 c .. 8 c + 7 (rows 0..127 = A, 128..255 = W);
+    // This wave's chunks of a slab: chunk c covers stage rows 8 c .. 8 c + 7 (rows 0..BM-1 = A, then 128 rows of W);
     // lane i fills 16-byte slot i % 8 of row i / 8 and fetches k-vector (slot ^ swz(row)) for it.
     const bf16_t* src[CPW];
 #pragma unroll
@@ -89,34 +95,37 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
             load_lds16(src[c] + (size_t)slab * BK, smem + stage * STAGE_BYTES + (wave + 4 * c) * 1024);
     };
 
-    f32x16 acc[2][2];   // [feature tile][token tile]
+    f32x16 acc[2][TMW];   // [feature tile][token tile]
 #pragma unroll
     for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-        for (int tm = 0; tm < 2; tm++)
+        for (int tm = 0; tm < TMW; tm++)
 #pragma unroll
             for (int i = 0; i < 16; i++) acc[fn][tm][i] = 0.f;
 
     // Fragment addresses inside a stage.  With the XOR swizzle the 16-byte slot of the read for k-step kk of
-    // MFMA tile t is (lane part) ^ 2 (kk ^ 2 t), so four per-lane bases per operand cover all sixteen reads of
-    // a slab and the tile row block (t * 32 rows) is an immediate offset.
+    // MFMA tile t is (lane part) ^ 2 (kk ^ 2 t), so four per-lane bases per operand cover all the reads of
+    // a slab and the tile row block (t * 32 rows) is an immediate offset.  (With 32 token rows per wave the
+    // wave's own row offset 32 wt also reaches bit 2 of the swizzle; it is folded into the lane part.)
     const int lb = (hi ^ lr ^ (lr >> 3)) & 7;
+    const int lb_a = TMW == 1 ? lb ^ (4 * wt) : lb;
     int a_base[4], w_base[4];
 #pragma unroll
     for (int c = 0; c < 4; c++) {
-        a_base[c] = (wt * 64 + lr) * ROWB + ((lb ^ (2 * c)) * 16);
+        a_base[c] = (wt * 32 * TMW + lr) * ROWB + ((lb_a ^ (2 * c)) * 16);
         w_base[c] = BM * ROWB + (wf * 64 + lr) * ROWB + ((lb ^ (2 * c)) * 16);
     }
-    // Ring of four fragment sets, one per k-step of a slab; the reads run two k-steps (8 MFMAs) ahead of their
-    // use, across the slab boundary.
-    bf16x8 af[4][2], wfr[4][2];
+    // Ring of four fragment sets, one per k-step of a slab; the reads run two k-steps ahead of their use,
+    // across the slab boundary.
+    bf16x8 af[4][TMW], wfr[4][2];
     auto read_set = [&](int stage, int kk) {
         const unsigned char* base = smem + stage * STAGE_BYTES;
 #pragma unroll
-        for (int t = 0; t < 2; t++) {
+        for (int t = 0; t < TMW; t++)
             af[kk][t] = *reinterpret_cast<const bf16x8*>(base + a_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+#pragma unroll
+        for (int t = 0; t < 2; t++)
             wfr[kk][t] = *reinterpret_cast<const bf16x8*>(base + w_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
-        }
     };
 
     // Main loop.  Slab s sits in stage s % 2.  ONE barrier per slab, before k-step 2: by then every wave has
@@ -145,10 +154,10 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
 #pragma unroll
             for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-                for (int tm = 0; tm < 2; tm++)
+                for (int tm = 0; tm < TMW; tm++)
                     acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[kk][fn], af[kk][tm], acc[fn][tm], 0, 0, 0);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {   // one fragment read between two MFMAs
+            for (int j = 0; j < 2 * TMW; j++) {   // fragment reads between the MFMAs
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
@@ -162,10 +171,10 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     __builtin_amdgcn_s_barrier();                          // every wave is done with the slab buffers
 
     // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
-    // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*64 + tm*32 + lr.
+    // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*32*TMW + tm*32 + lr.
     constexpr bool GEGLU = EPI == EPI_GEGLU;
     constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
-    constexpr int NPASS = F32OUT ? 2 : 1;            // an fp32 tile is staged in two 64-token halves
+    constexpr int NPASS = (F32OUT && TMW == 2) ? 2 : 1;   // a 128-token fp32 tile is staged in two 64-token halves
     constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
     constexpr int ROWS_PER_PASS = BM / NPASS;
     constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
@@ -192,9 +201,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
         }
         if (NPASS == 1 || wt == pass) {
 #pragma unroll
-            for (int tm = 0; tm < 2; tm++) {
-                const int trow = (NPASS == 1 ? wt * 64 : 0) + tm * 32 + lr;      // row inside the staging tile
-                const int r = row0 + wt * 64 + tm * 32 + lr;                     // global token row
+            for (int tm = 0; tm < TMW; tm++) {
+                const int trow = (NPASS == 1 ? wt * 32 * TMW : 0) + tm * 32 + lr;   // row inside the staging tile
+                const int r = row0 + wt * 32 * TMW + tm * 32 + lr;                  // global token row
                 const float* gate_row = nullptr;
                 if constexpr (EPI == EPI_GATE_RES) {
                     if (p.gate) gate_row = p.gate + (size_t)(min(r, m - 1) / p.rows_per_gate) * p.gate_stride;
@@ -265,13 +274,11 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(GemmGroup g, int tile
     }
 }
 
-template <typename OT, int EPI>
-int launch_epi(const GemmGroup& g, hipStream_t st) {
-    const int tile_cols = EPI == EPI_GEGLU ? BN / 2 : BN;
-    const int tiles_n = (g.n + tile_cols - 1) / tile_cols;
+template <typename OT, int EPI, int TMW>
+int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
+    constexpr int BM = Geo<TMW>::BM;
     const int tiles0 = ((g.p[0].m + BM - 1) / BM) * tiles_n;
     const int tiles1 = g.count > 1 ? ((g.p[1].m + BM - 1) / BM) * tiles_n : 0;
-    if (tiles0 + tiles1 == 0) return HYB_OK;
     char name[96];
     snprintf(name, sizeof(name), "gemm_mfma_%dx%d.epi%d.n%d.k%d", BM, BN, EPI, g.n, g.k);
     double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
@@ -280,11 +287,26 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
     if (tiles0 == 0) {  // keep problem 0 non-empty so that the tile -> problem split stays simple
         gg.p[0] = g.p[1];
         gg.count = 1;
-        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI>), dim3(tiles1), dim3(256), 0, st, gg, tiles_n, tiles1);
+        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(tiles1), dim3(256), 0, st, gg, tiles_n, tiles1);
     } else {
-        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI>), dim3(tiles0 + tiles1), dim3(256), 0, st, gg, tiles_n, tiles0);
+        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(tiles0 + tiles1), dim3(256), 0, st, gg, tiles_n, tiles0);
     }
     return hyb_check_launch("gemm_mfma");
+}
+
+// 128-token tiles unless they would fill less than three quarters of the 512 workgroup slots of the chip (two
+// per CU); then 64-token tiles, of which three fit a CU (768 slots), halve the length of the single round.
+constexpr int kSmallGridTiles = 384;
+
+template <typename OT, int EPI>
+int launch_epi(const GemmGroup& g, hipStream_t st) {
+    const int tile_cols = EPI == EPI_GEGLU ? BN / 2 : BN;
+    const int tiles_n = (g.n + tile_cols - 1) / tile_cols;
+    const int rows1 = g.count > 1 ? g.p[1].m : 0;
+    const int tiles128 = ((g.p[0].m + 127) / 128 + (rows1 + 127) / 128) * tiles_n;
+    if (tiles128 == 0) return HYB_OK;
+    if (tiles128 <= kSmallGridTiles && g.p[0].m + rows1 > 64) return launch_tiles<OT, EPI, 1>(g, tiles_n, st);
+    return launch_tiles<OT, EPI, 2>(g, tiles_n, st);
 }
 
 }  // namespace

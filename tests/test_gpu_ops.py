@@ -23,8 +23,9 @@ def _data(seed, shape, dt, std=1.0):
 
 
 # (m, n, k): ragged rows, several tiles, the real GEMM shapes' aspect; k a multiple of 64 for the MFMA
-# path, an odd k for the plain kernel (f32 only)
-LINEAR_SHAPES = [(1, 64, 64), (77, 128, 64), (333, 1536, 256), (300, 72, 128), (513, 384, 192)]
+# path, an odd k for the plain kernel (f32 only).  The MFMA kernel uses 64-row tiles for grids of at most 384
+# 128-row tiles and 128-row tiles beyond: the last shape (9 x 44 = 396 tiles, ragged both ways) takes the latter.
+LINEAR_SHAPES = [(1, 64, 64), (77, 128, 64), (333, 1536, 256), (300, 72, 128), (513, 384, 192), (1100, 5576, 128)]
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
