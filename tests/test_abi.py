@@ -74,3 +74,41 @@ def test_argument_validation_happens_before_any_gpu_work(lib):
     assert lib.hyb_branch_discrepancy(vp(16), vp(16), 1, 4096, 3, 0, vp(16), vp(256), 1 << 20, None) == 3
     lib.hyb_last_error_string.restype = ctypes.c_char_p
     assert b"p must be" in lib.hyb_last_error_string()
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes structures of the binding against sizeof / offsetof of the C declarations (compiled with gcc:
+    the header is plain C)."""
+    import shutil
+    import subprocess
+    from paper_2602_21760_amd import binding
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    structs = {"hyb_block_desc": binding.BlockDesc, "hyb_stream_weights": binding.StreamWeights,
+               "hyb_block_weights": binding.BlockWeights, "hyb_sdxl_block_desc": binding.SdxlBlockDesc,
+               "hyb_sdxl_block_weights": binding.SdxlBlockWeights, "hyb_switch_state": binding.SwitchState}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "hyb.h"', 'int main(void) {']
+    for cname, ct in structs.items():
+        lines.append('printf("%s size %%zu\\n", sizeof(%s));' % (cname, cname))
+        for fname, _ in ct._fields_:
+            lines.append('printf("%s %s %%zu\\n", offsetof(%s, %s));' % (cname, fname, cname, fname))
+    lines.append("return 0; }")
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    got = {tuple(l.split()[:2]): int(l.split()[2]) for l in out if l}
+    for cname, ct in structs.items():
+        assert got[(cname, "size")] == ctypes.sizeof(ct), cname
+        for fname, _ in ct._fields_:
+            assert got[(cname, fname)] == getattr(ct, fname).offset, (cname, fname)
+
+
+def test_missing_library_is_an_error(monkeypatch, tmp_path):
+    """No fallback: without libhyb.so the binding raises."""
+    from paper_2602_21760_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(Exception):
+        binding.lib()
