@@ -43,6 +43,7 @@ template <int TMW> struct Geo {
     static constexpr int CPW = STAGE_BYTES / 1024 / 4;     // 1 KB chunks per wave per slab (8 / 6)
     static constexpr int SMEM_BYTES = 2 * STAGE_BYTES;     // 64 KB -> two workgroups per CU / 48 KB -> three
 };
+constexpr int VEC_BYTES = 2 * BN * 4;           // the tile's bias and gate values, behind the slab buffers
 constexpr int OUT_STRIDE_B16 = BN * 2 + 16;     // staging row strides (bytes), padded against conflicts
 constexpr int OUT_STRIDE_F32 = BN * 4 + 16;
 
@@ -58,7 +59,7 @@ __device__ __forceinline__ void load_lds16(const void* g, void* l) {
 template <typename OT, int EPI, int TMW>
 __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
     constexpr int BM = Geo<TMW>::BM, STAGE_BYTES = Geo<TMW>::STAGE_BYTES, CPW = Geo<TMW>::CPW;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[Geo<TMW>::SMEM_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[Geo<TMW>::SMEM_BYTES + VEC_BYTES];
 
     int tile = blockIdx.x;
     const int pi = tile >= tiles0 ? 1 : 0;
@@ -133,14 +134,65 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // slab s + 2 right behind the barrier, and the copy of slab s + 1 (issued one slab earlier) is awaited just
     // before it, so that k-steps 2 and 3 can already fetch the first fragments of slab s + 1.
     const int nslab = k / BK;
-    issue(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // Epilogue operands are fetched where their latency is hidden.  Bias and gate of the tile's 128 columns:
+    // one value per thread now, parked in LDS behind the slab buffers once the first slab's wait has passed.
+    // (The gate row must be the same for all rows of the tile; tiles that straddle samples read it from
+    // global memory in the epilogue.)
+    float* vec_lds = reinterpret_cast<float*>(smem + Geo<TMW>::SMEM_BYTES);
+    bool gate_in_lds = false;
+    if constexpr (EPI == EPI_GATE_RES) {
+        if (p.gate) gate_in_lds = row0 / p.rows_per_gate == min(row0 + BM - 1, m - 1) / p.rows_per_gate;
+    }
+    {
+        const int t = tid % BN;
+        int f = min(col0 + t, n - 1);
+        if constexpr (EPI == EPI_GEGLU) f = t < 64 ? min(col0 + t, n - 1) : n + min(col0 + t - 64, n - 1);
+        float val = 0.f;
+        if (tid < BN) {
+            if (p.bias) val = p.bias[f];
+        } else if constexpr (EPI == EPI_GATE_RES) {
+            if (gate_in_lds) val = p.gate[(size_t)(row0 / p.rows_per_gate) * p.gate_stride + f];
+        }
+        issue(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        vec_lds[tid] = val;
+    }
     __builtin_amdgcn_s_barrier();
     if (nslab > 1) issue(1, 1);
     read_set(0, 0);
     read_set(0, 1);
+    constexpr bool GEGLU = EPI == EPI_GEGLU;
+    constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
+    constexpr int NPASS = (F32OUT && TMW == 2) ? 2 : 1;   // a 128-token fp32 tile is staged in two 64-token halves
+    constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
+    constexpr int ROWS_PER_PASS = BM / NPASS;
+    constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
+    constexpr int CHUNKS_PER_ROW = (GEGLU ? BN / 2 : BN) / CHUNK_ELEMS;
+    constexpr int SE = F32OUT ? 4 : 2;                  // bytes per staged element
+    constexpr int ITERS = ROWS_PER_PASS * CHUNKS_PER_ROW / 256;   // 16-byte chunks per thread per pass
+    // gate * y + residual: the residual chunks of a pass are fetched ahead (pass 0 during the last slab of the main
+    // loop, pass 1 before pass 0 is staged); loading them where they are used would expose their latency, and
+    // one by one between the stores they would serialise on every load (out may alias res).
+    constexpr bool RES = EPI == EPI_GATE_RES;
+    f32x4 resv[RES ? NPASS : 1][RES ? ITERS : 1];
+    auto load_res = [&](int pass) {
+        if constexpr (RES) {
+#pragma unroll
+            for (int j = 0; j < ITERS; j++) {
+                const int c = tid + 256 * j;
+                const int r = row0 + pass * ROWS_PER_PASS + c / CHUNKS_PER_ROW, f = col0 + (c % CHUNKS_PER_ROW) * CHUNK_ELEMS;
+                resv[pass][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (r < m && f < n) {
+                    const size_t o = (size_t)r * n + f;
+                    resv[pass][j] = *reinterpret_cast<const f32x4*>(p.res + o);
+                    if (p.res2) resv[pass][j] += *reinterpret_cast<const f32x4*>(p.res2 + o);
+                }
+            }
+        }
+    };
     auto slab_step = [&](int s, auto stage_tag) {
         constexpr int STG = decltype(stage_tag)::value;
+        if (s == nslab - 1) load_res(0);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; kk++) {
             if (kk == 2 && s + 1 < nslab) {
@@ -172,51 +224,41 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
 
     // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
     // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*32*TMW + tm*32 + lr.
-    constexpr bool GEGLU = EPI == EPI_GEGLU;
-    constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
-    constexpr int NPASS = (F32OUT && TMW == 2) ? 2 : 1;   // a 128-token fp32 tile is staged in two 64-token halves
-    constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
-    constexpr int ROWS_PER_PASS = BM / NPASS;
-    constexpr int CHUNK_ELEMS = 16 / (int)sizeof(OT);   // elements per 16-byte chunk
-    constexpr int CHUNKS_PER_ROW = (GEGLU ? BN / 2 : BN) / CHUNK_ELEMS;
-    constexpr int SE = F32OUT ? 4 : 2;                  // bytes per staged element
-    constexpr int ITERS = ROWS_PER_PASS * CHUNKS_PER_ROW / 256;   // 16-byte chunks per thread per pass
 #pragma unroll
     for (int pass = 0; pass < NPASS; pass++) {
-        // gate * y + residual: fetch this pass's residual chunks first, so that their latency overlaps the
-        // staging (loading them one by one between the stores serialises on every load: out may alias res)
-        f32x4 resv[EPI == EPI_GATE_RES ? ITERS : 1];
-        if constexpr (EPI == EPI_GATE_RES) {
-#pragma unroll
-            for (int j = 0; j < ITERS; j++) {
-                const int c = tid + 256 * j;
-                const int r = row0 + pass * ROWS_PER_PASS + c / CHUNKS_PER_ROW, f = col0 + (c % CHUNKS_PER_ROW) * CHUNK_ELEMS;
-                resv[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (r < m && f < n) {
-                    const size_t o = (size_t)r * n + f;
-                    resv[j] = *reinterpret_cast<const f32x4*>(p.res + o);
-                    if (p.res2) resv[j] += *reinterpret_cast<const f32x4*>(p.res2 + o);
-                }
-            }
-        }
+        if (pass == 0 && NPASS == 2) load_res(1);
         if (NPASS == 1 || wt == pass) {
+            // bias (and gate) of this lane's 8 column groups first, in one batch of LDS reads
+            f32x4 bv[2][4];
+#pragma unroll
+            for (int fn = 0; fn < 2; fn++)
+#pragma unroll
+                for (int gi = 0; gi < 4; gi++) bv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + wf * 64 + fn * 32 + 8 * gi + 4 * hi);
 #pragma unroll
             for (int tm = 0; tm < TMW; tm++) {
                 const int trow = (NPASS == 1 ? wt * 32 * TMW : 0) + tm * 32 + lr;   // row inside the staging tile
-                const int r = row0 + wt * 32 * TMW + tm * 32 + lr;                  // global token row
-                const float* gate_row = nullptr;
+                [[maybe_unused]] f32x4 gv[2][4];
                 if constexpr (EPI == EPI_GATE_RES) {
-                    if (p.gate) gate_row = p.gate + (size_t)(min(r, m - 1) / p.rows_per_gate) * p.gate_stride;
+                    const int r = row0 + wt * 32 * TMW + tm * 32 + lr;              // global token row
+                    // tiles whose rows do not share one gate row read it from global memory
+                    const float* gate_row = (p.gate && !gate_in_lds) ? p.gate + (size_t)(min(r, m - 1) / p.rows_per_gate) * p.gate_stride : nullptr;
+#pragma unroll
+                    for (int fn = 0; fn < 2; fn++)
+#pragma unroll
+                        for (int gi = 0; gi < 4; gi++) {
+                            const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;
+                            if (gate_in_lds) gv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + BN + fl);
+                            else if (gate_row) gv[fn][gi] = *reinterpret_cast<const f32x4*>(gate_row + min(col0 + fl, n - 4));   // clamped: masked on store
+                            else gv[fn][gi] = (f32x4){1.f, 1.f, 1.f, 1.f};
+                        }
                 }
 #pragma unroll
                 for (int fn = 0; fn < 2; fn++)
 #pragma unroll
                     for (int gi = 0; gi < 4; gi++) {
                         const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;      // feature inside the tile
-                        int f = min(col0 + fl, n - 4);                           // clamped: masked on store
-                        if constexpr (GEGLU) f = fl < 64 ? min(col0 + fl, n - 4) : n + min(col0 + fl - 64, n - 4);
                         f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
-                        if (p.bias) v += *reinterpret_cast<const f32x4*>(p.bias + f);
+                        v += bv[fn][gi];
                         if constexpr (EPI == EPI_GELU_TANH) {
 #pragma unroll
                             for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
@@ -224,7 +266,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
 #pragma unroll
                             for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
                         } else if constexpr (EPI == EPI_GATE_RES) {
-                            if (gate_row) v *= *reinterpret_cast<const f32x4*>(gate_row + f);
+                            v *= gv[fn][gi];
                         }
                         unsigned char* dst = smem + trow * STRIDE + fl * SE;
                         if constexpr (F32OUT) {
@@ -264,7 +306,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
             } else if constexpr (EPI == EPI_GATE_RES) {
                 const size_t o = (size_t)r * n + f;
-                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = *reinterpret_cast<const f32x4*>(srcp) + resv[j];
+                *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = *reinterpret_cast<const f32x4*>(srcp) + resv[pass][j];
             } else {
                 OT* dst = static_cast<OT*>(p.out) + (size_t)r * n + f;
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
