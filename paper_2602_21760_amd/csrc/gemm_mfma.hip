@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // (The gate row must be the same for all rows of the tile; tiles that straddle samples read it from
     // global memory in the epilogue.)
     float* vec_lds = reinterpret_cast<float*>(smem + Geo<TMW>::SMEM_BYTES);
-    bool gate_in_lds = false;
+    bool gate_in_lds = true;   // no gate: ones
     if constexpr (EPI == EPI_GATE_RES) {
         if (p.gate) gate_in_lds = row0 / p.rows_per_gate == min(row0 + BM - 1, m - 1) / p.rows_per_gate;
     }
@@ -151,7 +151,8 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
         if (tid < BN) {
             if (p.bias) val = p.bias[f];
         } else if constexpr (EPI == EPI_GATE_RES) {
-            if (gate_in_lds) val = p.gate[(size_t)(row0 / p.rows_per_gate) * p.gate_stride + f];
+            val = 1.f;
+            if (p.gate && gate_in_lds) val = p.gate[(size_t)(row0 / p.rows_per_gate) * p.gate_stride + f];
         }
         issue(0, 0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -171,22 +172,22 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     constexpr int SE = F32OUT ? 4 : 2;                  // bytes per staged element
     constexpr int ITERS = ROWS_PER_PASS * CHUNKS_PER_ROW / 256;   // 16-byte chunks per thread per pass
     // gate * y + residual: the residual chunks of a pass are fetched ahead (pass 0 during the last slab of the main
-    // loop, pass 1 before pass 0 is staged); loading them where they are used would expose their latency, and
+    // loop, pass 1 once pass 0 is staged); loading them where they are used would expose their latency, and
     // one by one between the stores they would serialise on every load (out may alias res).
     constexpr bool RES = EPI == EPI_GATE_RES;
     f32x4 resv[RES ? NPASS : 1][RES ? ITERS : 1];
     auto load_res = [&](int pass) {
         if constexpr (RES) {
-#pragma unroll
-            for (int j = 0; j < ITERS; j++) {
+            auto chunk_offset = [&](int j) {   // clamped like every other edge access: masked on store
                 const int c = tid + 256 * j;
-                const int r = row0 + pass * ROWS_PER_PASS + c / CHUNKS_PER_ROW, f = col0 + (c % CHUNKS_PER_ROW) * CHUNK_ELEMS;
-                resv[pass][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                if (r < m && f < n) {
-                    const size_t o = (size_t)r * n + f;
-                    resv[pass][j] = *reinterpret_cast<const f32x4*>(p.res + o);
-                    if (p.res2) resv[pass][j] += *reinterpret_cast<const f32x4*>(p.res2 + o);
-                }
+                const int r = min(row0 + pass * ROWS_PER_PASS + c / CHUNKS_PER_ROW, m - 1), f = min(col0 + (c % CHUNKS_PER_ROW) * CHUNK_ELEMS, n - 4);
+                return (size_t)r * n + f;
+            };
+#pragma unroll
+            for (int j = 0; j < ITERS; j++) resv[pass][j] = *reinterpret_cast<const f32x4*>(p.res + chunk_offset(j));
+            if (p.res2) {
+#pragma unroll
+                for (int j = 0; j < ITERS; j++) resv[pass][j] += *reinterpret_cast<const f32x4*>(p.res2 + chunk_offset(j));
             }
         }
     };
@@ -226,31 +227,34 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*32*TMW + tm*32 + lr.
 #pragma unroll
     for (int pass = 0; pass < NPASS; pass++) {
-        if (pass == 0 && NPASS == 2) load_res(1);
-        if (NPASS == 1 || wt == pass) {
+        // Staging; GATE_LDS: the gate values come from LDS (always, unless the tile's rows straddle gate rows).
+        [[maybe_unused]] const float* gate_ptr = p.gate;
+        [[maybe_unused]] const int gate_rows = p.rows_per_gate;
+        [[maybe_unused]] const size_t gate_stride = p.gate_stride;
+        auto stage = [&, gate_ptr, gate_rows, gate_stride](auto gate_lds_tag) {
+            constexpr bool GATE_LDS = decltype(gate_lds_tag)::value;
             // bias (and gate) of this lane's 8 column groups first, in one batch of LDS reads
             f32x4 bv[2][4];
+            [[maybe_unused]] f32x4 gv[2][4];
 #pragma unroll
             for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-                for (int gi = 0; gi < 4; gi++) bv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + wf * 64 + fn * 32 + 8 * gi + 4 * hi);
+                for (int gi = 0; gi < 4; gi++) {
+                    const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;
+                    bv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + fl);
+                    if constexpr (RES && GATE_LDS) gv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + BN + fl);
+                }
 #pragma unroll
             for (int tm = 0; tm < TMW; tm++) {
                 const int trow = (NPASS == 1 ? wt * 32 * TMW : 0) + tm * 32 + lr;   // row inside the staging tile
-                [[maybe_unused]] f32x4 gv[2][4];
-                if constexpr (EPI == EPI_GATE_RES) {
+                if constexpr (RES && !GATE_LDS) {
                     const int r = row0 + wt * 32 * TMW + tm * 32 + lr;              // global token row
-                    // tiles whose rows do not share one gate row read it from global memory
-                    const float* gate_row = (p.gate && !gate_in_lds) ? p.gate + (size_t)(min(r, m - 1) / p.rows_per_gate) * p.gate_stride : nullptr;
+                    const float* gate_row = gate_ptr + (size_t)(min(r, m - 1) / gate_rows) * gate_stride;
 #pragma unroll
                     for (int fn = 0; fn < 2; fn++)
 #pragma unroll
-                        for (int gi = 0; gi < 4; gi++) {
-                            const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;
-                            if (gate_in_lds) gv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + BN + fl);
-                            else if (gate_row) gv[fn][gi] = *reinterpret_cast<const f32x4*>(gate_row + min(col0 + fl, n - 4));   // clamped: masked on store
-                            else gv[fn][gi] = (f32x4){1.f, 1.f, 1.f, 1.f};
-                        }
+                        for (int gi = 0; gi < 4; gi++)   // column clamped: masked on store
+                            gv[fn][gi] = *reinterpret_cast<const f32x4*>(gate_row + min(col0 + wf * 64 + fn * 32 + 8 * gi + 4 * hi, n - 4));
                 }
 #pragma unroll
                 for (int fn = 0; fn < 2; fn++)
@@ -277,7 +281,12 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
                         }
                     }
             }
+        };
+        if (NPASS == 1 || wt == pass) {
+            if (!RES || gate_in_lds) stage(std::true_type{});
+            else stage(std::false_type{});
         }
+        if (pass == 0 && NPASS == 2) load_res(1);   // in flight across this pass's barrier and stores
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < ITERS; j++) {
