@@ -57,11 +57,19 @@ __device__ __forceinline__ void load_lds16(const void* g, void* l) {
 }
 
 template <typename OT, int EPI, int TMW>
-__global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0) {
+__global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0, int total, int xcd_run) {
     constexpr int BM = Geo<TMW>::BM, STAGE_BYTES = Geo<TMW>::STAGE_BYTES, CPW = Geo<TMW>::CPW;
     __shared__ __attribute__((aligned(16))) unsigned char smem[Geo<TMW>::SMEM_BYTES + VEC_BYTES];
 
+    // Workgroups go round-robin to the 8 XCDs (each with its own L2) in launch order.  With few tile columns the
+    // tiles that an XCD works on at a time then share hardly any operand panel (every 8th tile: all tile rows, a
+    // few columns), so XCD x is given the run of consecutive tiles [x * xcd_run, (x + 1) * xcd_run) instead
+    // (a few whole tile rows).  xcd_run == 0: plain order.
     int tile = blockIdx.x;
+    if (xcd_run > 0) {
+        tile = (tile % 8) * xcd_run + tile / 8;
+        if (tile >= total) return;
+    }
     const int pi = tile >= tiles0 ? 1 : 0;
     if (pi) tile -= tiles0;
     const GemmProblem& p = g.p[pi];
@@ -325,6 +333,9 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     }
 }
 
+// Up to this many tile columns a launch hands each XCD a run of consecutive tiles (see the kernel).
+constexpr int kNarrowTileCols = 16;
+
 template <typename OT, int EPI, int TMW>
 int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
     constexpr int BM = Geo<TMW>::BM;
@@ -335,13 +346,16 @@ int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
     double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
     HybTraceScope trace(name, "flop", 2.0 * rows * g.n * g.k, st);
     GemmGroup gg = g;
+    int t0 = tiles0;
     if (tiles0 == 0) {  // keep problem 0 non-empty so that the tile -> problem split stays simple
         gg.p[0] = g.p[1];
         gg.count = 1;
-        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(tiles1), dim3(256), 0, st, gg, tiles_n, tiles1);
-    } else {
-        hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(tiles0 + tiles1), dim3(256), 0, st, gg, tiles_n, tiles0);
+        t0 = tiles1;
     }
+    const int total = tiles0 + tiles1;
+    const int xcd_run = tiles_n <= kNarrowTileCols ? (total + 7) / 8 : 0;
+    const int grid = xcd_run ? 8 * xcd_run : total;
+    hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(grid), dim3(256), 0, st, gg, tiles_n, t0, total, xcd_run);
     return hyb_check_launch("gemm_mfma");
 }
 
