@@ -339,16 +339,23 @@ constexpr int kNarrowTileCols = 16;
 template <typename OT, int EPI, int TMW>
 int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
     constexpr int BM = Geo<TMW>::BM;
-    const int tiles0 = ((g.p[0].m + BM - 1) / BM) * tiles_n;
-    const int tiles1 = g.count > 1 ? ((g.p[1].m + BM - 1) / BM) * tiles_n : 0;
+    GemmGroup gg = g;
+    // The smaller problem goes first: its tiles fetch a whole weight matrix from HBM for few rows, which is better
+    // hidden under the start of the large problem than left for the end of the launch.
+    if (gg.count > 1 && gg.p[1].m < gg.p[0].m) {
+        const GemmProblem t = gg.p[0];
+        gg.p[0] = gg.p[1];
+        gg.p[1] = t;
+    }
+    const int tiles0 = ((gg.p[0].m + BM - 1) / BM) * tiles_n;
+    const int tiles1 = gg.count > 1 ? ((gg.p[1].m + BM - 1) / BM) * tiles_n : 0;
     char name[96];
     snprintf(name, sizeof(name), "gemm_mfma_%dx%d.epi%d.n%d.k%d", BM, BN, EPI, g.n, g.k);
     double rows = g.p[0].m + (g.count > 1 ? g.p[1].m : 0);
     HybTraceScope trace(name, "flop", 2.0 * rows * g.n * g.k, st);
-    GemmGroup gg = g;
     int t0 = tiles0;
     if (tiles0 == 0) {  // keep problem 0 non-empty so that the tile -> problem split stays simple
-        gg.p[0] = g.p[1];
+        gg.p[0] = gg.p[1];
         gg.count = 1;
         t0 = tiles1;
     }
