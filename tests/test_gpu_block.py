@@ -63,6 +63,16 @@ def test_block_ragged_reduced_size(hb, dt):
     assert rel_l2(g_img - x_img, r_img - x_img) < (5e-2 if dt == "bf16" else 1e-3)
 
 
+def test_block_with_more_text_than_image_tokens(hb):
+    # the text stream is the larger problem of every two-stream launch (the launch order of the two depends on
+    # their sizes); 3 samples, neither token count a multiple of a tile
+    cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=14, n_txt=211, ctx_dim=128, batch=3, dtype="bf16")
+    assert cfg.n_img == 49
+    g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=21)
+    assert rel_l2(g_img, r_img) < TOL_BF16 and rel_l2(g_txt, r_txt) < TOL_BF16
+    assert rel_l2(g_img - x_img, r_img - x_img) < 5e-2
+
+
 def test_block_batch_invariance_and_determinism(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=24, n_txt=33, ctx_dim=128, batch=2)
     a_img, a_txt, _, _, _ = _block_case(hb, cfg, seed=20, same_rows=True)
