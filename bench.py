@@ -157,6 +157,16 @@ def sdxl_workload(hb, model, synth, torch):
     return out
 
 
+def _device_info(torch):
+    """Static properties as the runtime reports them (the clock is the maximum, not the sustained one)."""
+    pr = torch.cuda.get_device_properties(0)
+    info = {"compute_units": pr.multi_processor_count, "hbm_gib": round(pr.total_memory / 2**30, 1)}
+    for name in ("gcnArchName", "clock_rate", "L2_cache_size"):
+        if hasattr(pr, name):
+            info[name] = getattr(pr, name)
+    return info
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -237,6 +247,7 @@ def main():
                                "4096+333 tokens, batch 1, one denoiser forward", "algorithmic_tflop_per_step": flops / 1e12},
         "roofline": roofline, "guidance_pass_roofline": guidance, "kernels": kernels, "other_workloads": secondary, "setup_s": round(setup_s, 1),
         "device": torch.cuda.get_device_name(0),
+        "device_info": _device_info(torch),
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, synth)
