@@ -2,9 +2,10 @@
 // W [n, k] features-out x features-in, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
 //
 // Tiling: a workgroup of 4 waves (2 x 2) owns a 128 x 128 output tile; each wave owns 2 x 2 MFMA
-// tiles of 32 x 32 (small problems: 64 x 128 tiles, 1 x 2 MFMA tiles per wave, see launch_epi).  The weight fragment is the MFMA "A" operand and the token fragment the "B"
-// operand, so the 16 accumulator registers of a lane run along the output-feature axis (4
-// consecutive features per group of 4 registers, one token per lane).
+// tiles of 32 x 32 (small problems: 64 x 128 tiles, 1 x 2 MFMA tiles per wave, see launch_epi).
+// The weight fragment is the MFMA "A" operand and the token fragment the "B" operand, so the 16
+// accumulator registers of a lane run along the output-feature axis (4 consecutive features per
+// group of 4 registers, one token per lane).
 //
 // Main loop: k is cut into slabs of 64.  A slab of both operands (128 + 128 rows of 128 bytes) is
 // copied global -> LDS by 16-byte direct-to-LDS loads (global_load_lds_dwordx4: a wave fills 1 KB of
@@ -21,10 +22,16 @@
 // buffers) and written out row-contiguously, 16 bytes per lane, so that global stores and the
 // residual reads are whole 128-byte lines.  (Storing straight from the MFMA layout issues 8-byte
 // pieces to 32 different rows per instruction; at these sizes that made the epilogue cost a third
-// of the tile time.)
+// of the tile time.)  What the epilogue reads from global memory is requested where the latency is
+// hidden: the tile's bias and gate values at the start of the tile (parked in LDS behind the slab
+// buffers), the residual during the last k-slab; every such access uses clamped addresses instead
+// of predicates, and the staging loops are free of branches.  (With a branch that chooses between
+// a global and an LDS source inside the loop, the compiler waits for ALL outstanding global loads
+// before every LDS read.)
 //
 // Up to two problems with the same (n, k) share a launch (image and text stream of a joint
-// block).  Ragged edges: row / feature indices are clamped on load and masked on store.  The
+// block), the smaller one first.  Tile order: plain, or one run of consecutive tiles per XCD when
+// there are few tile columns (see the kernel).  Ragged edges: row / feature indices are clamped on load and masked on store.  The
 // reduction order over k is fixed and a token's result does not depend on its tile row, so
 // results are deterministic and batch-invariant.
 #include "gemm.h"
