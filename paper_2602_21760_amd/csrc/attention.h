@@ -14,7 +14,13 @@ struct AttnArgs {
     float scale;     // > 0
     int q_stride;    // query rows stored per (batch, head) in q (>= n_q); 0 means n_q.  A larger stride lets a
                      // launch serve only the first n_q rows of a longer sequence (image-only queries over joint keys)
+    float* part;     // scratch of hyb_attention_split_bytes() for the MFMA kernel's split tail, or nullptr (no splitting)
+    // set by the launcher:
+    int tail_from, tail_units, tail_parts;
 };
+
+// Scratch the bf16 MFMA kernel wants for its split tail (see attention_mfma.hip); 0 when it would not split.
+size_t hyb_attention_split_bytes(int batch, int heads, int n_q);
 
 // Plain kernel (fp32 or bf16 storage, fp32 math with accurate expf).
 int hyb_launch_attention_simple(const AttnArgs& a, hyb_dtype dtype, hipStream_t st);

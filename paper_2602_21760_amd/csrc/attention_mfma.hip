@@ -29,6 +29,13 @@
 // bf16-rounded probabilities that enter the second contraction (v_dot2 with ones).
 // Tail keys are masked to -inf before the row maximum; tail query rows are clamped on load
 // and not stored.  The reduction order is fixed: results are deterministic and batch-invariant.
+//
+// Split tail.  All workgroups of a launch are usually resident at once (4 per CU), and a CU with 4 of
+// them takes a fifth longer than one with 3.  When an XCD holds a few more workgroups than a multiple
+// of its CU count (cfg 2: 105 on 32 CUs), those extra query blocks are therefore cut along the KEYS into
+// 2 or 3 workgroups each, which leave unnormalised partial results (output accumulator, reference
+// maximum, normaliser) in a scratch buffer; a small second kernel merges them in a fixed order.  The
+// busiest CUs then carry 3 1/3 workgroups instead of 4.
 #include "attention.h"
 
 #include <type_traits>
@@ -40,6 +47,7 @@ constexpr int BKV = 64;
 constexpr int ROWB = 128;                   // bytes per K / V row in LDS
 constexpr int TILE_BYTES = BKV * ROWB;      // 8 KB per operand tile
 constexpr float RESCALE_LOG2 = 8.0f;
+constexpr int PART_FLOATS = 34 * 256;       // per part of a split unit: 32 accumulator values, maximum, normaliser per thread
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef bf16x4 __attribute__((address_space(3)))* lds_bf16x4_ptr;
@@ -109,8 +117,17 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     // one L2 instead of being fetched into all eight.
     const int qblocks = (a.n_q + BQ - 1) / BQ, pairs = a.batch * a.heads;
     int pair, qb;
+    int part = 0, nparts = 1, unit = 0;   // split tail: this workgroup's share of the keys of query block `unit`
     if (pairs % 8 == 0) {
-        const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+        const int xcd = blockIdx.x % 8;
+        int j = blockIdx.x / 8;
+        if (a.tail_parts > 1 && j >= a.tail_from) {
+            const int e = j - a.tail_from;
+            nparts = a.tail_parts;
+            part = e % nparts;
+            unit = xcd * a.tail_units + e / nparts;
+            j = a.tail_from + e / nparts;
+        }
         pair = xcd + 8 * (j / qblocks);
         qb = j % qblocks;
     } else {
@@ -175,12 +192,13 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     }
 
     const int nt = (a.n_kv + BKV - 1) / BKV;
+    const int t_begin = part * nt / nparts, t_end = (part + 1) * nt / nparts;   // this workgroup's key tiles
     auto tile = [&](int t, auto buf_tag) {
         constexpr int BUF = decltype(buf_tag)::value;
         constexpr int BUF_OFF = BUF * 2 * TILE_BYTES;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile t has landed
         __builtin_amdgcn_s_barrier();                      // ... everyone's; and the other buffer is free again
-        if (t + 1 < nt) issue(t + 1, BUF ^ 1);
+        if (t + 1 < t_end) issue(t + 1, BUF ^ 1);
 
         // S^T = K Q^T: two accumulation chains (keys 0..31 / 32..63) interleaved; the K fragments flow through
         // a ring of four so that four LDS reads are always in flight ahead of the MFMA that needs them.
@@ -273,14 +291,24 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int hf = 0; hf < 2; hf++) o[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][kt][hf], pb[kt][hf], o[1], 0, 0, 0);
     };
-    issue(0, 0);
-    for (int t = 0; t < nt; t += 2) {
+    issue(t_begin, 0);
+    for (int t = t_begin; t < t_end; t += 2) {
         tile(t, std::integral_constant<int, 0>{});
-        if (t + 1 < nt) tile(t + 1, std::integral_constant<int, 1>{});
+        if (t + 1 < t_end) tile(t + 1, std::integral_constant<int, 1>{});
     }
 
     if (qrow >= a.n_q) return;
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (nparts > 1) {   // partial result of a split unit: merged by attention_merge_kernel
+        float* dst = a.part + ((size_t)unit * nparts + part) * PART_FLOATS + tid;
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) dst[(dt * 16 + i) * 256] = o[dt][i];
+        dst[32 * 256] = m_run;
+        dst[33 * 256] = l_tot;
+        return;
+    }
     const float inv = 1.0f / l_tot;
     const int hd = a.heads * 64;
     bf16_t* orow;
@@ -298,11 +326,109 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         }
 }
 
+// Merges the parts of the split tail units (one workgroup per unit, threads as in the main kernel): with
+// reference maxima m_p, normalisers l_p and accumulators o_p, the row is sum_p o_p 2^((m_p - M) c) over
+// sum_p l_p 2^((m_p - M) c), M = max_p m_p; parts in index order.
+template <int PARTS>
+__global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
+    const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+    const int lq = lane % 32, g = lane / 32;
+    const int qblocks = (a.n_q + BQ - 1) / BQ;
+    const int unit = blockIdx.x, xcd = unit / a.tail_units, j = a.tail_from + unit % a.tail_units;
+    const int pair = xcd + 8 * (j / qblocks), qb = j % qblocks;
+    const int h = pair % a.heads, b = pair / a.heads;
+    const int qrow = qb * BQ + wave * 32 + lq;
+    if (qrow >= a.n_q) return;
+    const float c = a.scale * 1.4426950408889634f;
+    const float* src = a.part + (size_t)unit * PARTS * PART_FLOATS + tid;
+    // everything this thread needs, requested at once
+    float val[PARTS][34];
+#pragma unroll
+    for (int p = 0; p < PARTS; p++)
+#pragma unroll
+        for (int i = 0; i < 34; i++) val[p][i] = src[p * PART_FLOATS + i * 256];
+    float m_all = val[0][32];
+#pragma unroll
+    for (int p = 1; p < PARTS; p++) m_all = fmaxf(m_all, val[p][32]);
+    float w[PARTS], l = 0.f;
+#pragma unroll
+    for (int p = 0; p < PARTS; p++) {
+        w[p] = __builtin_amdgcn_exp2f((val[p][32] - m_all) * c);
+        l = fmaf(val[p][33], w[p], l);
+    }
+    const float inv = 1.0f / l;
+    const int hd = a.heads * 64;
+    bf16_t* orow;
+    if (qrow < a.split) orow = static_cast<bf16_t*>(a.o) + ((size_t)b * a.split + qrow) * hd;
+    else orow = static_cast<bf16_t*>(a.o2) + ((size_t)b * (a.n_q - a.split) + (qrow - a.split)) * hd;
+    orow += h * 64;
+#pragma unroll
+    for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+        for (int gi = 0; gi < 4; gi++) {
+            float r[4];
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+                float acc = 0.f;
+#pragma unroll
+                for (int p = 0; p < PARTS; p++) acc = fmaf(val[p][dt * 16 + 4 * gi + e], w[p], acc);
+                r[e] = acc * inv;
+            }
+            bf16x4 ov = {(bf16_t)r[0], (bf16_t)r[1], (bf16_t)r[2], (bf16_t)r[3]};
+            *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * gi + 4 * g) = ov;
+        }
+}
+
+// Split decision for a launch: per XCD there are w workgroups (XCD-pinned order) on cus CUs with 4 slots each.
+struct TailSplit { int from, units, parts; };
+TailSplit tail_split(int batch, int heads, int n_q) {
+    TailSplit t = {0, 0, 1};
+    const int pairs = batch * heads;
+    if (pairs == 0 || pairs % 8 != 0) return t;
+    static int cus_per_xcd = 0;
+    if (cus_per_xcd == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = 256;
+        cus_per_xcd = cus / 8;
+    }
+    const int w = (pairs / 8) * ((n_q + BQ - 1) / BQ);
+    if (w > 4 * cus_per_xcd) return t;                  // more than one round: the hardware balances
+    const int full = w / cus_per_xcd * cus_per_xcd, extra = w - full;
+    if (full == 0 || extra == 0) return t;
+    int parts = cus_per_xcd / extra;                    // the parts of all extra blocks fit one more workgroup per CU
+    if (parts > 3) parts = 3;
+    if (parts < 2) return t;
+    t.from = full; t.units = extra; t.parts = parts;
+    return t;
+}
+
 }  // namespace
 
-int hyb_launch_attention_mfma(const AttnArgs& a, hipStream_t st) {
-    dim3 grid(((a.n_q + BQ - 1) / BQ) * a.heads * a.batch), block(256);
-    HybTraceScope trace("attention_mfma", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
-    hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, a);
-    return hyb_check_launch("attention_mfma");
+size_t hyb_attention_split_bytes(int batch, int heads, int n_q) {
+    const TailSplit t = tail_split(batch, heads, n_q);
+    return t.parts > 1 ? (size_t)8 * t.units * t.parts * PART_FLOATS * sizeof(float) : 0;
+}
+
+int hyb_launch_attention_mfma(const AttnArgs& a0, hipStream_t st) {
+    AttnArgs a = a0;
+    a.tail_from = a.tail_units = 0;
+    a.tail_parts = 1;
+    int blocks = ((a.n_q + BQ - 1) / BQ) * a.heads * a.batch;
+    // the split needs the scratch, whole key tiles for every part, and text rows that are stored (o2) if there are any
+    const TailSplit t = a.part ? tail_split(a.batch, a.heads, a.n_q) : TailSplit{0, 0, 1};
+    if (t.parts > 1 && (a.n_kv + BKV - 1) / BKV >= 2 * t.parts) {
+        a.tail_from = t.from; a.tail_units = t.units; a.tail_parts = t.parts;
+        blocks = 8 * (t.from + t.units * t.parts);
+    }
+    dim3 grid(blocks), block(256);
+    {
+        HybTraceScope trace("attention_mfma", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
+        hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, a);
+    }
+    int rc = hyb_check_launch("attention_mfma");
+    if (rc != HYB_OK || a.tail_parts == 1) return rc;
+    HybTraceScope trace("attention_merge", "byte", 8.0 * a.tail_units * a.tail_parts * PART_FLOATS * 4, st);
+    if (a.tail_parts == 2) hipLaunchKernelGGL(attention_merge_kernel<2>, dim3(8 * a.tail_units), block, 0, st, a);
+    else hipLaunchKernelGGL(attention_merge_kernel<3>, dim3(8 * a.tail_units), block, 0, st, a);
+    return hyb_check_launch("attention_merge");
 }

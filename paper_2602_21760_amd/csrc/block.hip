@@ -15,7 +15,7 @@ int hyb_launch_layernorm_pair(const float* const x[2], const float* const shift[
 namespace {
 
 struct BlockLayout {
-    size_t h_img, h_txt, q, k, v, o_img, o_txt, mlp_img, mlp_txt, total;
+    size_t h_img, h_txt, q, k, v, o_img, o_txt, mlp_img, mlp_txt, attn_part, total;
 };
 
 BlockLayout block_layout(const hyb_block_desc& d) {
@@ -37,6 +37,14 @@ BlockLayout block_layout(const hyb_block_desc& d) {
     L.o_txt = take(B * Nt * D);
     L.mlp_img = take(B * Ni * D * d.mlp_ratio);
     L.mlp_txt = take(B * Nt * D * d.mlp_ratio);
+    // scratch of the attention kernel's split tail (bf16 path only; sized for image-only queries too, which
+    // never need more)
+    L.attn_part = off;
+    if (d.dtype == HYB_BF16) {
+        const size_t joint = hyb_attention_split_bytes(d.batch, d.heads, d.n_img + d.n_txt);
+        const size_t img_only = hyb_attention_split_bytes(d.batch, d.heads, d.n_img);
+        off += hyb_align_up(joint > img_only ? joint : img_only, 256);
+    }
     L.total = off;
     return L;
 }
@@ -139,6 +147,7 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
     // 3. joint attention; image rows go to o_img, text rows to o_txt
     {
         AttnArgs a = {ws + L.q, ws + L.k, ws + L.v, o[0], o[1], Ni, B, d.heads, N, N, 0.125f, N};
+        if (L.total > L.attn_part) a.part = reinterpret_cast<float*>(ws + L.attn_part);
         if (!has_img) { a.o = o[1]; a.o2 = nullptr; a.split = N; }
         if (!has_txt) { a.o2 = nullptr; a.split = N; }
         if (txt_pre_only) { a.n_q = Ni; a.o2 = nullptr; a.split = Ni; }   // image queries only, joint keys

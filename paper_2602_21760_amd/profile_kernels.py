@@ -1,5 +1,5 @@
-"""Driver for hardware-counter runs: launches a calibration copy, the fused guidance pass, attention and the
-GEMM shapes of the SD3-shaped 1024x1024 workload through the C entry points (see profiles/)."""
+"""Driver for hardware-counter runs: launches a calibration copy, the fused guidance pass, attention, the GEMM
+shapes and one joint block of the SD3-shaped 1024x1024 workload through the C entry points (see profiles/)."""
 import sys, os
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))  # repo root
 import torch
@@ -41,5 +41,20 @@ for n_, k_, epi in ((4608, 1536, hb.HYB_EPI_BIAS), (6144, 1536, hb.HYB_EPI_GELU_
     kw = dict(residual=res) if epi == hb.HYB_EPI_GATE_RESIDUAL else {}
     for _ in range(3):
         hb.hyb_linear(a, w, bias, out, epi, **kw)
+torch.cuda.synchronize()
+# one joint block of the same workload through hyb_block_forward: there the attention kernel may split its last
+# query blocks along the keys (it has the block's workspace for the partial results) and a merge kernel follows
+from paper_2602_21760_amd import synth
+cfg = synth.CFG2
+D = cfg.hidden
+wnp = synth.mmdit_block_weights(cfg, 0)
+devw = {s: {n_: torch.from_numpy(a_).cuda().to(torch.bfloat16 if n_.endswith("_w") else torch.float32) for n_, a_ in wnp[s].items()
+            if not n_.startswith("ada_")} for s in wnp}
+desc = hb.block_desc(1, cfg.n_img, cfg.n_txt, D, cfg.heads, hb.HYB_BF16)
+ws = torch.empty(max(hb.hyb_block_workspace_bytes(desc), 256), device="cuda", dtype=torch.uint8)
+xi, xt = torch.randn(1, cfg.n_img, D, device="cuda"), torch.randn(1, cfg.n_txt, D, device="cuda")
+mod = torch.randn(1, 12 * D, device="cuda") * 0.1
+for _ in range(3):
+    hb.hyb_block_forward(desc, hb.block_weights(devw["img"], devw["txt"]), xi, xt, mod, mod[:, 6 * D:], 12 * D, xi, xt, ws)
 torch.cuda.synchronize()
 print("done")

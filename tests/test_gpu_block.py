@@ -73,6 +73,18 @@ def test_block_with_more_text_than_image_tokens(hb):
     assert rel_l2(g_img - x_img, r_img - x_img) < 5e-2
 
 
+def test_block_attention_with_split_tail(hb):
+    # 8 (batch, head) pairs, 40 query blocks each: one pair per XCD, 8 blocks more than a multiple of the 32 CUs
+    # of an XCD, so the attention kernel cuts those 8 blocks along the keys and merges the parts afterwards
+    cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=142, n_txt=77, ctx_dim=128, batch=2, dtype="bf16")
+    assert cfg.n_img + cfg.n_txt == 5118
+    g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=31)
+    assert rel_l2(g_img, r_img) < TOL_BF16 and rel_l2(g_txt, r_txt) < TOL_BF16
+    assert rel_l2(g_img - x_img, r_img - x_img) < 5e-2
+    # the split query blocks are the last 8 of every pair: image rows 4096 .. 5040 and the text rows
+    assert rel_l2(g_img[:, 4096:] - x_img[:, 4096:], r_img[:, 4096:] - x_img[:, 4096:]) < 5e-2
+
+
 def test_block_batch_invariance_and_determinism(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=24, n_txt=33, ctx_dim=128, batch=2)
     a_img, a_txt, _, _, _ = _block_case(hb, cfg, seed=20, same_rows=True)
