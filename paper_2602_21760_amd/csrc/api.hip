@@ -60,13 +60,13 @@ HybTraceScope::HybTraceScope(const char* kernel, const char* unit, double work, 
     slot = (int)g_used++;
     g_recs[slot].key = key;
     g_recs[slot].work = work;
-    hipEventRecord(g_recs[slot].e0, st);
+    (void)hipEventRecord(g_recs[slot].e0, st);
 }
 
 HybTraceScope::~HybTraceScope() {
     if (slot < 0) return;
     std::lock_guard<std::mutex> lk(g_tmx);
-    hipEventRecord(g_recs[slot].e1, st);
+    (void)hipEventRecord(g_recs[slot].e1, st);
 }
 
 extern "C" int hyb_trace_enable(int on) {

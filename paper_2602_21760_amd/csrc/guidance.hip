@@ -14,7 +14,6 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kVec = 8;                          // elements per thread per iteration
 constexpr int kIters = 1;                        // one vector per thread: the smallest workgroups stream fastest (5.8 vs 5.5 TB/s with two)
-constexpr int kChunk = kThreads * kVec * kIters; // elements per workgroup
 
 template <typename T, int V> struct Vec;
 template <> struct Vec<float, 8> {

@@ -36,9 +36,10 @@ struct LnArgs {
 template <typename OT, bool AFFINE>
 __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
     const int wave = threadIdx.x / HYB_WAVE, lane = threadIdx.x % HYB_WAVE;
-    const int set = blockIdx.x >= a.blocks0 ? 1 : 0;
+    const int blk = (int)blockIdx.x;
+    const int set = blk >= a.blocks0 ? 1 : 0;
     const LnSet& p = a.s[set];
-    const int row = (blockIdx.x - (set ? a.blocks0 : 0)) * 4 + wave;
+    const int row = (blk - (set ? a.blocks0 : 0)) * 4 + wave;
     if (row >= p.rows) return;
     const float* __restrict__ x = p.x;
     const float* __restrict__ shift = p.shift;
