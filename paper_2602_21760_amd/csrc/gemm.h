@@ -38,6 +38,9 @@ struct GemmGroup {
     GemmProblem p[kMaxGroup];
     int count;
     int n, k;
+    // Scratch for the MFMA path's k split (single problem, few tiles, long k: see gemm_mfma.hip), or nullptr.
+    void* splitk_ws;
+    size_t splitk_bytes;
 };
 
 // Plain tiled FMA kernel: any shape, fp32 or bf16 operands, fp32 accumulation.

@@ -64,7 +64,7 @@ __device__ __forceinline__ void load_lds16(const void* g, void* l) {
 }
 
 template <typename OT, int EPI, int TMW>
-__global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0, int total, int xcd_run) {
+__global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGroup g, int tiles_n, int tiles0, int total, int xcd_run, int ksplit) {
     constexpr int BM = Geo<TMW>::BM, STAGE_BYTES = Geo<TMW>::STAGE_BYTES, CPW = Geo<TMW>::CPW;
     __shared__ __attribute__((aligned(16))) unsigned char smem[Geo<TMW>::SMEM_BYTES + VEC_BYTES];
 
@@ -76,6 +76,13 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     if (xcd_run > 0) {
         tile = (tile % 8) * xcd_run + tile / 8;
         if (tile >= total) return;
+    }
+    // k split (ksplit > 1, single problem, plain fp32 output): ksplit consecutive workgroups share a tile; each
+    // multiplies its share of the k-slabs and writes the raw sums to its own [m, n] plane of p.out
+    int split = 0;
+    if (ksplit > 1) {
+        split = tile % ksplit;
+        tile /= ksplit;
     }
     const int pi = tile >= tiles0 ? 1 : 0;
     if (pi) tile -= tiles0;
@@ -148,7 +155,10 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // issued (and, after the lgkmcnt wait, completed) all its reads of slab s, so stage s % 2 can be refilled with
     // slab s + 2 right behind the barrier, and the copy of slab s + 1 (issued one slab earlier) is awaited just
     // before it, so that k-steps 2 and 3 can already fetch the first fragments of slab s + 1.
-    const int nslab = k / BK;
+    const int slab0 = split * (k / BK) / ksplit;
+    const int nslab = (split + 1) * (k / BK) / ksplit - slab0;
+#pragma unroll
+    for (int c = 0; c < CPW; c++) src[c] += (size_t)slab0 * BK;
     // Epilogue operands are fetched where their latency is hidden.  Bias and gate of the tile's 128 columns:
     // one value per thread now, parked in LDS behind the slab buffers once the first slab's wait has passed.
     // (The gate row must be the same for all rows of the tile; tiles that straddle samples read it from
@@ -332,7 +342,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
                 const size_t o = (size_t)r * n + f;
                 *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + o) = *reinterpret_cast<const f32x4*>(srcp) + resv[pass][j];
             } else {
-                OT* dst = static_cast<OT*>(p.out) + (size_t)r * n + f;
+                OT* dst = static_cast<OT*>(p.out) + (size_t)split * m * n + (size_t)r * n + f;
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
             }
         }
@@ -344,7 +354,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
 constexpr int kNarrowTileCols = 16;
 
 template <typename OT, int EPI, int TMW>
-int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
+int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st, int ksplit = 1) {
     constexpr int BM = Geo<TMW>::BM;
     GemmGroup gg = g;
     // The smaller problem goes first: its tiles fetch a whole weight matrix from HBM for few rows, which is better
@@ -366,11 +376,41 @@ int launch_tiles(const GemmGroup& g, int tiles_n, hipStream_t st) {
         gg.count = 1;
         t0 = tiles1;
     }
-    const int total = tiles0 + tiles1;
+    const int total = (tiles0 + tiles1) * ksplit;
     const int xcd_run = tiles_n <= kNarrowTileCols ? (total + 7) / 8 : 0;
     const int grid = xcd_run ? 8 * xcd_run : total;
-    hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(grid), dim3(256), 0, st, gg, tiles_n, t0, total, xcd_run);
+    hipLaunchKernelGGL((gemm_mfma_kernel<OT, EPI, TMW>), dim3(grid), dim3(256), 0, st, gg, tiles_n, t0, total, xcd_run, ksplit);
     return hyb_check_launch("gemm_mfma");
+}
+
+// Second pass of the k split: out = epilogue(sum over the planes, in order, + bias), one thread per element.
+template <typename OT>
+__global__ __launch_bounds__(256) void gemm_splitk_merge_kernel(GemmGroup g, const float* planes, int ksplit, int epi) {
+    const GemmProblem& p = g.p[0];
+    const size_t total = (size_t)p.m * g.n;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int r = (int)(i / g.n), c = (int)(i % g.n);
+    float v = planes[i];
+    for (int s = 1; s < ksplit; s++) v += planes[(size_t)s * total + i];
+    if (p.bias) v += p.bias[c];
+    gemm_store_scalar<OT>(p, epi, g.n, r, c, v);
+}
+
+// k split for launches that cannot fill the chip with tiles but have a long k (each workgroup then waits for
+// one k-slab after the other: the time is slabs x slab latency whatever the chip could do).  Returns the number
+// of splits (1: none): as many as keep every workgroup resident at once (768 slots of 64-row tiles) with at
+// least 4 slabs each, at most 8, and only when the caller's scratch holds the planes.  (slots: 512 for 128-row
+// tiles, 768 for 64-row tiles.)
+constexpr int kSplitMinSlabs = 32;
+int choose_ksplit(const GemmGroup& g, int tiles, int slots) {
+    const int nslab = g.k / BK;
+    if (g.count != 1 || !g.splitk_ws || nslab < kSplitMinSlabs || tiles <= 0) return 1;
+    int s = slots / tiles;
+    if (s > nslab / 4) s = nslab / 4;
+    if (s > 8) s = 8;
+    if (s < 2 || (size_t)s * g.p[0].m * g.n * sizeof(float) > g.splitk_bytes) return 1;
+    return s;
 }
 
 // 128-token tiles unless they would fill less than three quarters of the 512 workgroup slots of the chip (two
@@ -384,6 +424,29 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
     const int rows1 = g.count > 1 ? g.p[1].m : 0;
     const int tiles128 = ((g.p[0].m + 127) / 128 + (rows1 + 127) / 128) * tiles_n;
     if (tiles128 == 0) return HYB_OK;
+    if constexpr (EPI != EPI_GEGLU) {
+        // 128-row tiles stream a third fewer operand bytes: preferred whenever they allow a split at all
+        int ksplit = 1;
+        bool tall = false;
+        if (tiles128 <= kSmallGridTiles) {
+            ksplit = choose_ksplit(g, tiles128, 512);
+            tall = ksplit > 1;
+            if (!tall) ksplit = choose_ksplit(g, ((g.p[0].m + 63) / 64) * tiles_n, 768);
+        }
+        if (ksplit > 1) {
+            // pass 1: raw fp32 sums of every k share (plain epilogue, no bias), pass 2: merge + the real epilogue
+            GemmGroup part = g;
+            part.p[0].bias = nullptr;
+            part.p[0].out = g.splitk_ws;
+            int rc = tall ? launch_tiles<float, EPI_BIAS, 2>(part, tiles_n, st, ksplit) : launch_tiles<float, EPI_BIAS, 1>(part, tiles_n, st, ksplit);
+            if (rc != HYB_OK) return rc;
+            const size_t elems = (size_t)g.p[0].m * g.n;
+            HybTraceScope trace("gemm_splitk_merge", "byte", (double)elems * (4.0 * ksplit + sizeof(OT)), st);
+            hipLaunchKernelGGL((gemm_splitk_merge_kernel<OT>), dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, g,
+                               static_cast<const float*>(g.splitk_ws), ksplit, EPI);
+            return hyb_check_launch("gemm_splitk_merge");
+        }
+    }
     if (tiles128 <= kSmallGridTiles && g.p[0].m + rows1 > 64) return launch_tiles<OT, EPI, 1>(g, tiles_n, st);
     return launch_tiles<OT, EPI, 2>(g, tiles_n, st);
 }

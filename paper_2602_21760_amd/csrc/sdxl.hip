@@ -17,7 +17,7 @@ size_t hyb_groupnorm_scratch_bytes(int batch, int groups);
 namespace {
 
 struct SdxlLayout {
-    size_t g, h, q, k, v, o, ck, cv, ff, gn, total;
+    size_t g, h, q, k, v, o, ck, cv, ff, gn, splitk, splitk_bytes, total;
 };
 
 SdxlLayout sdxl_layout(const hyb_sdxl_block_desc& d) {
@@ -40,6 +40,10 @@ SdxlLayout sdxl_layout(const hyb_sdxl_block_desc& d) {
     L.cv = take(B * S * C * es);
     L.ff = take(B * T * 4 * C * es);    // GEGLU output
     L.gn = take(hyb_groupnorm_scratch_bytes(d.batch, d.groups));
+    // fp32 planes of the GEMMs' k split: up to 8 for the context K/V projection (few rows), 3 for the down-projection
+    const size_t kv_planes = 8 * B * S * 2 * C * 4, ff2_planes = 3 * B * T * C * 4;
+    L.splitk_bytes = kv_planes > ff2_planes ? kv_planes : ff2_planes;
+    L.splitk = take(L.splitk_bytes);
     L.total = off;
     return L;
 }
@@ -92,6 +96,7 @@ extern "C" int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb
     auto one = [&](int m, int n, int k) {
         GemmGroup gg = {};
         gg.count = 1; gg.n = n; gg.k = k; gg.p[0].m = m;
+        gg.splitk_ws = ws + L.splitk; gg.splitk_bytes = L.splitk_bytes;
         return gg;
     };
     auto attn = [&](void* q, void* k, void* v, int n_kv) {
