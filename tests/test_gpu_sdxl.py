@@ -80,6 +80,22 @@ def test_sdxl_stage_real_shapes_one_block(hb, stage):
     assert rel_l2(got - x, ref - x) < 5e-2
 
 
+def test_sdxl_block_is_deterministic_with_split_k(hb):
+    """At the stage B shape the context K/V projection and the down-projection split their k range over several
+    workgroups per tile; the partial sums are added in a fixed order, so two runs agree bit for bit."""
+    from paper_2602_21760_amd import model
+    cfg = synth.CFG5B
+    w = synth.sdxl_block_weights(cfg, 0)
+    x, ctx = synth.sdxl_inputs(cfg)
+    st = model.SDXLStage(cfg, [w])
+    outs = []
+    for _ in range(2):
+        dx = dev(x)
+        st.forward(dx, dev(ctx))
+        outs.append(host(dx))
+    assert np.array_equal(outs[0], outs[1])
+
+
 @pytest.mark.timeout(600)
 @pytest.mark.parametrize("stage", ["A", "B"])
 def test_sdxl_stage_2048_shapes_sampled_rows(hb, stage):
