@@ -19,8 +19,9 @@ cases, brute force and invariants in the CPU tests).
 Pins (tests/test_oracle_*.py): torch CPU fp64 library routines (layer_norm, group_norm,
 gelu, silu, scaled_dot_product_attention), pure-Python brute force on tiny inputs,
 closed forms (CFG s=0/1, discrepancy of scaled branches, Euler telescoping, sigma
-closed form) and structural invariants (zero modulation => identity block, key
-permutation invariance, softmax rows sum to one).
+closed form, constant velocity through the whole sampling loop) and structural invariants
+(zero modulation => identity block, key permutation invariance, softmax rows sum to one,
+a guidance branch with zero weight does not matter).
 """
 import math
 
