@@ -164,14 +164,17 @@ __global__ __launch_bounds__(256) void adaln_kernel(const WT* __restrict__ w, co
 // ------------------------------------------------------------------------------------------
 // GroupNorm on token-major data x[B, T, C], groups of C/G consecutive channels, statistics over
 // (T, C/G) per sample.  Three kernels; 1 and 3 use one thread per 4-channel vector (so every load and
-// store is a coalesced 16-byte access and a thread stays inside one group):
+// store is a coalesced 16-byte access and a thread stays inside one group) and chunks of a few tokens, so
+// that a launch has thousands of workgroups with all their loads in flight at once:
 //  1. each workgroup sums x and x^2 over its chunk of tokens (fp32 per thread, then the threads of a
 //     group are added in a fixed order in fp64) -> partial[b][chunk][group][2];
-//  2. one workgroup per sample adds the partials in chunk order (fp64) and forms mean and 1/std per group;
+//  2. one workgroup per sample adds the partials (fp64; a few interleaved partial sums per group, each in
+//     chunk order, then those in lane order) and forms mean and 1/std per group;
 //  3. each workgroup normalises its chunk: y = (x - mean) rstd gamma + beta.
 // No atomics: the result is deterministic and independent of the batch index.
 // ------------------------------------------------------------------------------------------
-constexpr int kGnChunks = 128;
+constexpr int kGnChunks = 1024;   // at most this many chunks per sample
+constexpr int kGnTokens = 4;      // tokens per chunk (more when a sample has more than kGnChunks * kGnTokens tokens)
 
 __global__ void groupnorm_stats_kernel(const float* __restrict__ x, double* __restrict__ partial, int tokens,
                                        int channels, int groups, int tokens_per_chunk) {
@@ -181,10 +184,18 @@ __global__ void groupnorm_stats_kernel(const float* __restrict__ x, double* __re
     const int t0 = chunk * tokens_per_chunk, t1 = min(tokens, t0 + tokens_per_chunk);
     const f32x4* xb = reinterpret_cast<const f32x4*>(x + (size_t)b * tokens * channels);
     float s = 0.f, q = 0.f;
-    for (int t = t0; t < t1; t++) {
-        const f32x4 v = xb[(size_t)t * nvec + vec];
-        s += (v[0] + v[1]) + (v[2] + v[3]);
-        q = fmaf(v[0], v[0], q); q = fmaf(v[1], v[1], q); q = fmaf(v[2], v[2], q); q = fmaf(v[3], v[3], q);
+    for (int t = t0; t < t1; t += kGnTokens) {
+        f32x4 v[kGnTokens];
+#pragma unroll
+        for (int j = 0; j < kGnTokens; j++) v[j] = xb[(size_t)min(t + j, t1 - 1) * nvec + vec];   // clamped: in bounds
+#pragma unroll
+        for (int j = 0; j < kGnTokens; j++) {
+            if (t + j < t1) {
+                s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+                q = fmaf(v[j][0], v[j][0], q); q = fmaf(v[j][1], v[j][1], q);
+                q = fmaf(v[j][2], v[j][2], q); q = fmaf(v[j][3], v[j][3], q);
+            }
+        }
     }
     gn_red[2 * vec] = s;
     gn_red[2 * vec + 1] = q;
@@ -202,18 +213,33 @@ __global__ void groupnorm_stats_kernel(const float* __restrict__ x, double* __re
     }
 }
 
-// One workgroup per sample, one thread per group: adds the chunk partials in chunk order (fp64) and leaves
-// (mean, 1/std) as two floats per group.
+// One workgroup per sample, `lanes` threads per group, thread = j * groups + g so that the threads of a wave
+// read consecutive (sum, sum of squares) pairs: thread (g, j) adds the partials of chunks j, j + lanes, ... in
+// that order (fp64), thread (g, 0) then adds the `lanes` sums in lane order and leaves (mean, 1/std) as two
+// floats per group.  blockDim.x = groups * lanes.
 __global__ void groupnorm_finalize_kernel(const double* __restrict__ partial, float* __restrict__ stats, int nchunks,
-                                          int groups, double count, float eps) {
-    const int g = threadIdx.x, b = blockIdx.x;
-    if (g >= groups) return;
-    const double* p = partial + ((size_t)b * nchunks * groups + g) * 2;
+                                          int groups, int lanes, double count, float eps) {
+    typedef double f64x2 __attribute__((ext_vector_type(2)));
+    extern __shared__ double gn_fin[];   // [lanes][groups][2]
+    const int g = threadIdx.x % groups, j = threadIdx.x / groups, b = blockIdx.x;
+    const f64x2* p = reinterpret_cast<const f64x2*>(partial) + (size_t)b * nchunks * groups + g;
     double ds = 0.0, dq = 0.0;
-#pragma unroll 8
-    for (int c = 0; c < nchunks; c++) {
-        ds += p[(size_t)c * groups * 2];
-        dq += p[(size_t)c * groups * 2 + 1];
+    for (int c0 = j; c0 < nchunks; c0 += 8 * lanes) {     // eight loads in flight, added in chunk order
+        f64x2 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) v[u] = p[(size_t)min(c0 + u * lanes, nchunks - 1) * groups];   // clamped: in bounds
+#pragma unroll
+        for (int u = 0; u < 8; u++)
+            if (c0 + u * lanes < nchunks) { ds += v[u][0]; dq += v[u][1]; }
+    }
+    gn_fin[(j * groups + g) * 2] = ds;
+    gn_fin[(j * groups + g) * 2 + 1] = dq;
+    __syncthreads();
+    if (j != 0) return;
+    ds = 0.0; dq = 0.0;
+    for (int i = 0; i < lanes; i++) {
+        ds += gn_fin[(i * groups + g) * 2];
+        dq += gn_fin[(i * groups + g) * 2 + 1];
     }
     const double mean_d = ds / count;
     const double var_d = fmax(dq / count - mean_d * mean_d, 0.0);
@@ -233,12 +259,19 @@ __global__ void groupnorm_apply_kernel(const float* __restrict__ x, const float*
     const f32x4* xb = reinterpret_cast<const f32x4*>(x + (size_t)b * tokens * channels);
     f32x4* ob = reinterpret_cast<f32x4*>(out + (size_t)b * tokens * channels);
     const int t0 = chunk * tokens_per_chunk, t1 = min(tokens, t0 + tokens_per_chunk);
-    for (int t = t0; t < t1; t++) {
-        const f32x4 v = xb[(size_t)t * nvec + vec];
-        f32x4 y;
+    for (int t = t0; t < t1; t += kGnTokens) {
+        f32x4 v[kGnTokens];
 #pragma unroll
-        for (int j = 0; j < 4; j++) y[j] = fmaf((v[j] - mean) * rstd, gm[j], bt[j]);
-        ob[(size_t)t * nvec + vec] = y;
+        for (int j = 0; j < kGnTokens; j++) v[j] = xb[(size_t)min(t + j, t1 - 1) * nvec + vec];   // clamped: in bounds
+#pragma unroll
+        for (int j = 0; j < kGnTokens; j++) {
+            if (t + j < t1) {
+                f32x4 y;
+#pragma unroll
+                for (int e = 0; e < 4; e++) y[e] = fmaf((v[j][e] - mean) * rstd, gm[e], bt[e]);
+                ob[(size_t)(t + j) * nvec + vec] = y;
+            }
+        }
     }
 }
 
@@ -342,15 +375,18 @@ int hyb_launch_groupnorm(const float* x, const float* gamma, const float* beta, 
     HYB_REQUIRE(channels % (4 * groups) == 0 && channels <= 4096 && groups <= channels / 4, HYB_ERR_SHAPE,
                 "groupnorm: channels %d must be a multiple of 4 * groups (%d) and at most 4096", channels, groups);
     const int nvec = channels / 4;
-    const int nchunks = tokens < kGnChunks ? tokens : kGnChunks;
+    const int want = (tokens + kGnTokens - 1) / kGnTokens;
+    const int nchunks = want < kGnChunks ? want : kGnChunks;
     const int tpc = (tokens + nchunks - 1) / nchunks;
-    const int used = (tokens + tpc - 1) / tpc;     // chunks that actually hold tokens
+    const int used = (tokens + tpc - 1) / tpc;     // chunks that actually hold tokens (<= kGnChunks)
     dim3 grid(used, batch), block(nvec);
     HybTraceScope trace("groupnorm", "byte", (double)batch * tokens * channels * 12, st);
     hipLaunchKernelGGL(groupnorm_stats_kernel, grid, block, nvec * 2 * sizeof(float), st, x, (double*)scratch, tokens, channels, groups, tpc);
     float* stats = reinterpret_cast<float*>(static_cast<char*>(scratch) + gn_partial_bytes(batch, groups));
-    hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(batch), dim3(64 * ((groups + 63) / 64)), 0, st, (const double*)scratch, stats, used, groups,
-                       (double)tokens * (channels / groups), eps);
+    int lanes = 32;                                   // groups * lanes <= 1024 threads
+    while (groups * lanes > 1024) lanes /= 2;
+    hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(batch), dim3(groups * lanes), groups * lanes * 2 * sizeof(double), st,
+                       (const double*)scratch, stats, used, groups, lanes, (double)tokens * (channels / groups), eps);
     hipLaunchKernelGGL(groupnorm_apply_kernel, grid, block, 0, st, x, (const float*)stats, gamma, beta, out, tokens, channels, groups, tpc);
     return hyb_check_launch("groupnorm");
 }

@@ -19,7 +19,7 @@ def hb():
     return binding
 
 
-@pytest.mark.parametrize("shape", [(2, 37, 640), (1, 300, 1280), (3, 5, 128), (2, 1, 256)])
+@pytest.mark.parametrize("shape", [(2, 37, 640), (1, 300, 1280), (3, 5, 128), (2, 1, 256), (1, 5003, 128), (2, 4096, 640)])
 def test_groupnorm(hb, shape):
     B, T, C = shape
     x = synth.normal(80, shape, 2.0, "f32") + 0.7
