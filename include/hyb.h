@@ -55,7 +55,8 @@ typedef enum {
     HYB_EPI_BIAS = 0,          /* out = a w^T + bias                                          */
     HYB_EPI_GELU_TANH = 1,     /* out = GELUtanh(a w^T + bias)                                */
     HYB_EPI_SILU = 2,          /* out = SiLU(a w^T + bias)                                    */
-    HYB_EPI_GATE_RESIDUAL = 3  /* out(fp32) = residual + gate[row / rows_per_gate] * (a w^T + bias) */
+    HYB_EPI_GATE_RESIDUAL = 3, /* out(fp32) = residual + gate[row / rows_per_gate] * (a w^T + bias) */
+    HYB_EPI_GEGLU = 5          /* out = (a wu^T + bias[:n]) * GELUerf(a wg^T + bias[n:]), w = [wu; wg] of 2n rows */
 } hyb_epilogue;
 
 int hyb_version(void);                       /* major * 10000 + minor * 100 + patch */
@@ -141,6 +142,8 @@ int hyb_layernorm_modulate(const float* x, const float* shift, const float* scal
  * bias: device float[n] or NULL; out: device [m, n] of `out_dtype` (fp32 required for
  * HYB_EPI_GATE_RESIDUAL).  residual: device float[m, n] (may alias out); gate: device float,
  * element (row r, column j) at gate[(r / rows_per_gate) * gate_stride + j], or NULL for gate 1.
+ * HYB_EPI_GEGLU (the gated feed-forward of the SDXL-shaped block): w is [2n, k], rows [0, n) the value half and
+ * rows [n, 2n) the gate half, bias float[2n] or NULL, exact (erf) GELU on the gate.
  * k % 8 == 0 and n % 8 == 0 for bf16.  m == 0 is a no-op. */
 int hyb_linear(const void* a, const void* w, const float* bias, void* out, int m, int n, int k,
                hyb_dtype dtype, hyb_dtype out_dtype, hyb_epilogue epi,

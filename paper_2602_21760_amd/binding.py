@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "libhyb.so")
 
 HYB_F32, HYB_BF16 = 0, 1
 HYB_NORM_L1, HYB_NORM_L2 = 1, 2
-HYB_EPI_BIAS, HYB_EPI_GELU_TANH, HYB_EPI_SILU, HYB_EPI_GATE_RESIDUAL = 0, 1, 2, 3
+HYB_EPI_BIAS, HYB_EPI_GELU_TANH, HYB_EPI_SILU, HYB_EPI_GATE_RESIDUAL, HYB_EPI_GEGLU = 0, 1, 2, 3, 5
 STATUS = {0: "HYB_OK", 1: "HYB_ERR_NULL", 2: "HYB_ERR_SHAPE", 3: "HYB_ERR_DTYPE", 4: "HYB_ERR_ALIGN",
           5: "HYB_ERR_WORKSPACE", 6: "HYB_ERR_LAUNCH"}
 
@@ -221,9 +221,9 @@ def hyb_layernorm_modulate(x, shift, scale, mod_stride, out, eps):
 
 
 def hyb_linear(a, w, bias, out, epi=HYB_EPI_BIAS, residual=None, gate=None, rows_per_gate=1, gate_stride=0):
-    """a: [m, k]; w: [n, k]; out: [m, n]."""
+    """a: [m, k]; w: [n, k] (HYB_EPI_GEGLU: [2n, k]); out: [m, n]."""
     m, k = a.shape
-    n = w.shape[0]
+    n = out.shape[1]
     pg = None if gate is None else C.c_void_p(gate.data_ptr())
     _check(lib().hyb_linear(_p(a), _p(w, a.dtype), _p(bias, torch.float32), _p(out), m, n, k, _dt(a), _dt(out), epi,
                             _p(residual, torch.float32), pg, rows_per_gate, gate_stride, _stream()))

@@ -106,7 +106,7 @@ extern "C" int hyb_linear(const void* a, const void* w, const float* bias, void*
                           const float* residual, const float* gate, int rows_per_gate, size_t gate_stride,
                           void* stream) {
     HYB_CHECK_DTYPE(dtype); HYB_CHECK_DTYPE(out_dtype);
-    HYB_REQUIRE(epi >= HYB_EPI_BIAS && epi <= HYB_EPI_GATE_RESIDUAL, HYB_ERR_DTYPE, "hyb_linear: unknown epilogue %d", (int)epi);
+    HYB_REQUIRE((epi >= HYB_EPI_BIAS && epi <= HYB_EPI_GATE_RESIDUAL) || epi == HYB_EPI_GEGLU, HYB_ERR_DTYPE, "hyb_linear: unknown epilogue %d", (int)epi);
     HYB_REQUIRE(m >= 0 && n >= 0 && k >= 0, HYB_ERR_SHAPE, "hyb_linear: negative size");
     if (m == 0 || n == 0) return HYB_OK;
     HYB_CHECK_PTR(a); HYB_CHECK_PTR(w); HYB_CHECK_PTR(out);

@@ -74,6 +74,11 @@ def test_argument_validation_happens_before_any_gpu_work(lib):
     assert lib.hyb_branch_discrepancy(vp(16), vp(16), 1, 4096, 3, 0, vp(16), vp(256), 1 << 20, None) == 3
     lib.hyb_last_error_string.restype = ctypes.c_char_p
     assert b"p must be" in lib.hyb_last_error_string()
+    # hyb_linear: epilogue values are 0..3 and 5 (HYB_EPI_GEGLU); m == 0 is a no-op for every valid one
+    lib.hyb_linear.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, vp, vp, i, sz, vp]
+    for epi, want in ((0, 0), (3, 0), (5, 0), (4, 3), (6, 3), (-1, 3)):
+        assert lib.hyb_linear(None, None, None, None, 0, 64, 64, 1, 1, epi, None, None, 1, 0, None) == want, epi
+    assert lib.hyb_linear(None, vp(16), None, vp(16), 8, 64, 64, 1, 1, 5, None, None, 1, 0, None) == 1    # NULL a
 
 
 def test_struct_layouts_match_the_header(tmp_path):

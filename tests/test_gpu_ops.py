@@ -57,6 +57,24 @@ def test_linear_epilogues(hb, dt, shape):
     assert rel_l2(host(out), O.linear(a, w)) < tol(dt)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(77, 64, 64), (333, 200, 128), (1100, 2560, 192), (45, 37, 24)])
+def test_linear_geglu(hb, dt, shape):
+    """out = (a Wu^T + bu) * GELUerf(a Wg^T + bg), W = [Wu; Wg]: the gated feed-forward projection of the
+    SDXL-shaped block through the public entry point (MFMA kernel for bf16 with k % 64 == 0, plain kernel else)."""
+    m, n, k = shape
+    a, w, b = _data(1, (m, k), dt), _data(2, (2 * n, k), dt, 0.08), _data(3, (2 * n,), "f32", 0.5)
+    da, dw, db = dev(a, tdt(dt)), dev(w, tdt(dt)), dev(b)
+    ref = O.linear(a, w[:n], b[:n]) * O.gelu_erf(O.linear(a, w[n:], b[n:]))
+    for od in ("f32", dt):
+        out = torch.empty(m, n, device="cuda", dtype=tdt(od))
+        hb.hyb_linear(da, dw, db, out, hb.HYB_EPI_GEGLU)
+        assert rel_l2(host(out), ref) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
+    out = torch.empty(m, n, device="cuda", dtype=tdt(dt))
+    hb.hyb_linear(da, dw, None, out, hb.HYB_EPI_GEGLU)                       # no bias
+    assert rel_l2(host(out), O.linear(a, w[:n]) * O.gelu_erf(O.linear(a, w[n:]))) < max(tol(dt), 4e-3)
+
+
 def test_linear_odd_k_f32(hb):
     m, n, k = 45, 37, 19
     a, w, b = _data(1, (m, k), "f32"), _data(2, (n, k), "f32"), _data(3, (n,), "f32")
