@@ -3,7 +3,8 @@
 //
 // A workgroup of 4 waves owns 128 query rows of one (batch, head); each wave owns 32 of them.
 // Keys / values are streamed 64 at a time through double-buffered LDS tiles shared by the waves,
-// copied global -> LDS by 16-byte direct-to-LDS loads (no VGPR staging); rows are 128 bytes,
+// copied global -> LDS by 16-byte direct-to-LDS buffer loads (no VGPR staging; the tile's offset is a scalar
+// operand, the per-lane offset a loop invariant, so a tile costs no address arithmetic); rows are 128 bytes,
 // unpadded, with their 16-byte slots XOR-swizzled against bank conflicts: K rows (read one row per
 // lane, 16 bytes each) by (row ^ row >> 3) & 7, V rows (read by transposing loads, 8 keys x 64 bytes
 // per instruction) by 4 * (row >> 1 & 1).
@@ -148,16 +149,37 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 
     // Tile copy: 16 chunks of 1 KB (8 rows) per tile pair, 4 per wave: chunks w, w+4 of K and of V.
     // Lane i fills slot i % 8 of row i / 8 of its chunk with feature vector (slot ^ swz(row)) (V: swz_v).
+    // Buffer loads: the per-lane byte offset inside a tile is constant, the tile's offset is a scalar, so a
+    // tile costs no vector arithmetic.  Only a ragged last tile uses per-lane offsets with clamped rows
+    // (masked in the scores); every address is inside the pair's K / V rows.
     const int cp_row = lane / 8;
-    auto issue = [&](int t, int buf) {
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kp, 0, a.n_kv * ROWB, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vp, 0, a.n_kv * ROWB, 0x00020000);
+    int koff[2], voff[2];
 #pragma unroll
-        for (int c = 0; c < 2; c++) {
-            const int r = (wave + 4 * c) * 8 + cp_row;                       // row inside the tile
-            const size_t grow = (size_t)min(t * BKV + r, a.n_kv - 1);        // clamped; masked in the scores
-            const int fk = (lane % 8) ^ swz(r), fv = (lane % 8) ^ swz_v(r);
-            unsigned char* dst = smem[buf] + (wave + 4 * c) * 1024;
-            __builtin_amdgcn_global_load_lds((gptr_t)(kp + grow * 64 + fk * 8), (lptr_t)dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr_t)(vp + grow * 64 + fv * 8), (lptr_t)(dst + TILE_BYTES), 16, 0, 0);
+    for (int c = 0; c < 2; c++) {
+        const int r = (wave + 4 * c) * 8 + cp_row;                           // row inside the tile
+        koff[c] = r * ROWB + (((lane % 8) ^ swz(r)) * 16);
+        voff[c] = r * ROWB + (((lane % 8) ^ swz_v(r)) * 16);
+    }
+    const int last_full = a.n_kv / BKV;     // tiles below this index hold 64 valid keys
+    auto issue = [&](int t, int buf) {
+        if (t < last_full) {
+#pragma unroll
+            for (int c = 0; c < 2; c++) {
+                unsigned char* dst = smem[buf] + (wave + 4 * c) * 1024;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)dst, 16, koff[c], t * TILE_BYTES, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(dst + TILE_BYTES), 16, voff[c], t * TILE_BYTES, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 2; c++) {
+                const int r = (wave + 4 * c) * 8 + cp_row;
+                const int rc = min(t * BKV + r, a.n_kv - 1);                  // clamped row of the pair
+                unsigned char* dst = smem[buf] + (wave + 4 * c) * 1024;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lptr_t)dst, 16, rc * ROWB + (((lane % 8) ^ swz(r)) * 16), 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lptr_t)(dst + TILE_BYTES), 16, rc * ROWB + (((lane % 8) ^ swz_v(r)) * 16), 0, 0, 0);
+            }
         }
     };
 
