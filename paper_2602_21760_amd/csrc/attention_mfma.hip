@@ -264,14 +264,14 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         }
         // v_max3_f32 directly: fmaxf() makes the compiler canonicalise every MFMA output first (one extra
         // multiply per score), which costs more than the maxima themselves
-        float mx = s[0][0];
+        float mx = s[0][0], my = s[1][0];      // two chains: half the dependent latency
 #pragma unroll
-        for (int i = 1; i < 16; i += 3) {
+        for (int i = 1; i < 15; i += 2) {
             mx = max3(mx, s[0][i], s[0][i + 1]);
-            mx = max3(mx, s[0][i + 2], s[1][i]);
-            mx = max3(mx, s[1][i + 1], s[1][i + 2]);
+            my = max3(my, s[1][i], s[1][i + 1]);
         }
-        mx = max_with_other_half(max3(mx, s[1][0], s[1][0]));
+        mx = max3(mx, s[0][15], s[1][15]);
+        mx = max_with_other_half(max3(mx, my, my));
         // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
         const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
         if (__any(grow)) {
