@@ -8,9 +8,10 @@
 // group of 4 registers, one token per lane).
 //
 // Main loop: k is cut into slabs of 64.  A slab of both operands (128 + 128 rows of 128 bytes) is
-// copied global -> LDS by 16-byte direct-to-LDS loads (global_load_lds_dwordx4: a wave fills 1 KB of
-// LDS per instruction, no VGPR staging, no ds_write), double buffered: the copy of slab s + 1 runs
-// while slab s is multiplied.  LDS rows are unpadded; the 16-byte slots of a row are XOR-swizzled
+// copied global -> LDS by 16-byte direct-to-LDS buffer loads (buffer_load_dwordx4 ... lds: a wave fills 1 KB
+// of LDS per instruction, no VGPR staging, no ds_write; the slab's byte offset is the scalar operand and the
+// per-lane offsets are loop invariants, so a slab costs no vector address arithmetic), double buffered: the copy
+// of slab s + 1 runs while slab s is multiplied.  LDS rows are unpadded; the 16-byte slots of a row are XOR-swizzled
 // with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 16 consecutive rows hit distinct
 // banks (the swizzle is applied on the global side: each lane picks which 16 bytes it fetches).
 // Waits on the copies are explicit (s_waitcnt vmcnt + s_barrier); a full __syncthreads() would
@@ -59,8 +60,12 @@ typedef void __attribute__((address_space(3)))* lptr_t;
 
 __device__ __forceinline__ int swz(int r) { return (r ^ (r >> 3)) & 7; }
 
-__device__ __forceinline__ void load_lds16(const void* g, void* l) {
-    __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
+// 16 bytes per lane from a raw buffer (base address, size in bytes) straight into LDS: lane i's bytes land at
+// lds + 16 i; the address is base + voffset (per lane) + soffset (scalar).  Not a template: the descriptor type
+// only exists in the device pass.
+__device__ __forceinline__ void buffer_load_lds16(const void* base, unsigned bytes, void* lds, int voffset, int soffset) {
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lptr_t)lds, 16, voffset, soffset, 0, 0);
 }
 
 template <typename OT, int EPI, int TMW>
@@ -101,21 +106,36 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
 
     // This wave's chunks of a slab: chunk c covers stage rows 8 c .. 8 c + 7 (rows 0..BM-1 = A, then 128 rows of W);
     // lane i fills 16-byte slot i % 8 of row i / 8 and fetches k-vector (slot ^ swz(row)) for it.
-    const bf16_t* src[CPW];
+    // Buffer loads: a tile's A rows and W rows are two buffers that start at the tile's first row (so per-lane
+    // byte offsets are small 32-bit numbers, loop invariants), the k-slab's offset is a scalar operand: a slab costs
+    // no vector address arithmetic.  Rows past the end are clamped to the last row (their products are not stored).
+    const int slab0 = split * (k / BK) / ksplit;
+    const int nslab = (split + 1) * (k / BK) / ksplit - slab0;
+    const size_t row_tile_bytes = (size_t)k * 2;
+    const bf16_t* a_tile = A + (size_t)row0 * k;
+    const unsigned a_tile_bytes = (unsigned)(min(BM, m - row0) * row_tile_bytes);
+    const int w_rows = min(EPI == EPI_GEGLU ? BN / 2 : BN, n - col0);
+    const bf16_t* w_tile = W + (size_t)col0 * k;
+    const unsigned w_tile_bytes = (unsigned)((EPI == EPI_GEGLU ? (size_t)n + w_rows : (size_t)w_rows) * row_tile_bytes);
+    int voff[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; c++) {
         const int r = (wave + 4 * c) * 8 + lane / 8;
         const int kv = (lane % 8) ^ swz(r);
-        if (r < BM) src[c] = A + (size_t)min(row0 + r, m - 1) * k + kv * 8;
+        if (r < BM) voff[c] = (min(row0 + r, m - 1) - row0) * (int)row_tile_bytes + kv * 16;
         else if constexpr (EPI == EPI_GEGLU) {
             const int vr = r - BM;
-            src[c] = W + (size_t)(vr < 64 ? min(col0 + vr, n - 1) : n + min(col0 + vr - 64, n - 1)) * k + kv * 8;
-        } else src[c] = W + (size_t)min(col0 + r - BM, n - 1) * k + kv * 8;
+            voff[c] = (vr < 64 ? min(col0 + vr, n - 1) - col0 : n + min(col0 + vr - 64, n - 1) - col0) * (int)row_tile_bytes + kv * 16;
+        } else voff[c] = (min(col0 + r - BM, n - 1) - col0) * (int)row_tile_bytes + kv * 16;
     }
     auto issue = [&](int slab, int stage) {
+        const int soff = (slab0 + slab) * (BK * 2);
 #pragma unroll
-        for (int c = 0; c < CPW; c++)
-            load_lds16(src[c] + (size_t)slab * BK, smem + stage * STAGE_BYTES + (wave + 4 * c) * 1024);
+        for (int c = 0; c < CPW; c++) {
+            // chunks of A come first: chunk index wave + 4 c < BM / 8 exactly for c < BM / 32
+            if (c < BM / 32) buffer_load_lds16(a_tile, a_tile_bytes, smem + stage * STAGE_BYTES + (wave + 4 * c) * 1024, voff[c], soff);
+            else buffer_load_lds16(w_tile, w_tile_bytes, smem + stage * STAGE_BYTES + (wave + 4 * c) * 1024, voff[c], soff);
+        }
     };
 
     f32x16 acc[2][TMW];   // [feature tile][token tile]
@@ -155,10 +175,6 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // issued (and, after the lgkmcnt wait, completed) all its reads of slab s, so stage s % 2 can be refilled with
     // slab s + 2 right behind the barrier, and the copy of slab s + 1 (issued one slab earlier) is awaited just
     // before it, so that k-steps 2 and 3 can already fetch the first fragments of slab s + 1.
-    const int slab0 = split * (k / BK) / ksplit;
-    const int nslab = (split + 1) * (k / BK) / ksplit - slab0;
-#pragma unroll
-    for (int c = 0; c < CPW; c++) src[c] += (size_t)slab0 * BK;
     // Epilogue operands are fetched where their latency is hidden.  Bias and gate of the tile's 128 columns:
     // one value per thread now, parked in LDS behind the slab buffers once the first slab's wait has passed.
     // (The gate row must be the same for all rows of the tile; tiles that straddle samples read it from
@@ -455,6 +471,10 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
 
 int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st) {
     if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || g.n < 8) return -1;
+    // per-lane byte offsets inside a tile's operand buffers are 32-bit: up to 128 rows of k elements, and for the
+    // gated epilogue the gate rows n rows further down
+    if ((size_t)g.k * 2 * 256 >= ((size_t)1 << 31)) return -1;
+    if (epi == EPI_GEGLU && ((size_t)g.n + 128) * g.k * 2 >= ((size_t)1 << 31)) return -1;
     for (int i = 0; i < g.count; i++) {
         const GemmProblem& p = g.p[i];
         if (epi == EPI_GATE_RES && p.gate && (p.gate_stride % 4 != 0)) return -1;
