@@ -111,22 +111,22 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     // no vector address arithmetic.  Rows past the end are clamped to the last row (their products are not stored).
     const int slab0 = split * (k / BK) / ksplit;
     const int nslab = (split + 1) * (k / BK) / ksplit - slab0;
-    const size_t row_tile_bytes = (size_t)k * 2;
+    const size_t row_bytes = (size_t)k * 2;
     const bf16_t* a_tile = A + (size_t)row0 * k;
-    const unsigned a_tile_bytes = (unsigned)(min(BM, m - row0) * row_tile_bytes);
+    const unsigned a_tile_bytes = (unsigned)(min(BM, m - row0) * row_bytes);
     const int w_rows = min(EPI == EPI_GEGLU ? BN / 2 : BN, n - col0);
     const bf16_t* w_tile = W + (size_t)col0 * k;
-    const unsigned w_tile_bytes = (unsigned)((EPI == EPI_GEGLU ? (size_t)n + w_rows : (size_t)w_rows) * row_tile_bytes);
+    const unsigned w_tile_bytes = (unsigned)((EPI == EPI_GEGLU ? (size_t)n + w_rows : (size_t)w_rows) * row_bytes);
     int voff[CPW];
 #pragma unroll
     for (int c = 0; c < CPW; c++) {
         const int r = (wave + 4 * c) * 8 + lane / 8;
         const int kv = (lane % 8) ^ swz(r);
-        if (r < BM) voff[c] = (min(row0 + r, m - 1) - row0) * (int)row_tile_bytes + kv * 16;
+        if (r < BM) voff[c] = (min(row0 + r, m - 1) - row0) * (int)row_bytes + kv * 16;
         else if constexpr (EPI == EPI_GEGLU) {
             const int vr = r - BM;
-            voff[c] = (vr < 64 ? min(col0 + vr, n - 1) - col0 : n + min(col0 + vr - 64, n - 1) - col0) * (int)row_tile_bytes + kv * 16;
-        } else voff[c] = (min(col0 + r - BM, n - 1) - col0) * (int)row_tile_bytes + kv * 16;
+            voff[c] = (vr < 64 ? min(col0 + vr, n - 1) - col0 : n + min(col0 + vr - 64, n - 1) - col0) * (int)row_bytes + kv * 16;
+        } else voff[c] = (min(col0 + r - BM, n - 1) - col0) * (int)row_bytes + kv * 16;
     }
     auto issue = [&](int slab, int stage) {
         const int soff = (slab0 + slab) * (BK * 2);
