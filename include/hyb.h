@@ -123,6 +123,18 @@ int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
                         int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
                         hyb_dtype dtype, void* stream);
 
+/* The same attention with a caller-provided scratch buffer.  With it the bf16 kernel may cut the query
+ * blocks that would overload some compute units into parts along the keys and merge the unnormalised
+ * partial results (accumulator, maximum, normaliser) in a second kernel, in a fixed order: the result is
+ * deterministic, equal to hyb_joint_attention's up to the rounding of the merge, and the launch is
+ * shorter (this is the form hyb_block_forward uses).  workspace: device, at least
+ * hyb_joint_attention_workspace_bytes(batch, heads, n_q, dtype) bytes (0 for shapes that are never
+ * split and for HYB_F32: workspace may then be NULL), contents irrelevant on entry. */
+int hyb_joint_attention_ws(const void* q, const void* k, const void* v, void* o,
+                           int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
+                           hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dtype dtype);
+
 /* out[b, r] = sum_k w[r, k] * SiLU(temb[b, k]) + bias[r]: the adaLN modulation vectors of any
  * number of blocks / streams at once (stack their weight matrices along rows).
  * w: device [rows, hidden] of `dtype`; bias: device float[rows]; temb: device float[batch, hidden];
@@ -269,8 +281,10 @@ size_t hyb_sdxl_block_workspace_bytes(const hyb_sdxl_block_desc* desc);
  * Steps are counted upwards in sampling order, i = 0 .. total_steps - 1.  With the discrepancy M_i
  * of step i (Eq. 1, from hyb_branch_discrepancy / hyb_cfg_disc_euler), the slope over the last
  * `window` steps is read as the rate of decline G_i = (M[i - window] - M[i]) / window; tau1 is the
- * first i >= window with 0 <= G_i < g_slope, capped by tau_cap (and set to tau_cap when step
- * tau_cap is reached without the test firing); tau2 = tau1 + k.  Stage of step i: 0 = warm-up
+ * first i >= window with 0 <= G_i < g_slope, capped by cap = min(tau_cap, total_steps - 1 - k) (and
+ * set to cap when step cap is reached without the test firing); tau2 = tau1 + k.  The cap keeps
+ * Eq. 3's bound 1 <= k < total_steps - tau1 for every history, so tau2 is always a step of the run;
+ * k > total_steps - 1 is HYB_ERR_SHAPE.  Stage of step i: 0 = warm-up
  * (i <= tau1 or tau1 not yet known), 1 = parallelism (tau1 < i < tau2), 2 = fully-connecting.
  * The paper's settings: SDXL window 12, g_slope 0.4e-3, k 5, tau_cap 15; SD3 15, 0.1e-3, 5, 40.
  * ---------------------------------------------------------------------------------------- */

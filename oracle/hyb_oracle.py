@@ -427,21 +427,31 @@ def sampling_loop(latent, ctx_c, ctx_u, P, blocks_fn, heads, patch, T, shift, s)
 # Adaptive switching rule (Sec. 4.3, Eq. 2-3, Alg. 1), in ascending step index i = 0..T-1
 # --------------------------------------------------------------------------------------
 def switching_points(M, L, g_slope, tau_cap, k):
-    """Given the discrepancy history M[0..T-1] in sampling order, return (tau1, tau2).
+    """Given the discrepancy history M[0..T-1] in sampling order (T = len(M)), return (tau1, tau2).
 
     The slope over the last L steps is taken as the rate of decline G_i = (M[i-L] - M[i]) / L
     (Eq. 2 read on an ascending step index so that a falling curve gives G >= 0).  tau1' is the
-    first i >= L with 0 <= G_i < g_slope; tau1 = min(tau1', tau_cap), and tau1 = tau_cap when
-    the test never fires (safety cap); tau2 = tau1 + k (Eq. 3)."""
+    first i >= L with 0 <= G_i < g_slope; tau1 = min(tau1', cap), and tau1 = cap when the test
+    never fires (safety cap); tau2 = tau1 + k (Eq. 3).
+
+    Eq. 3 bounds the interval by 1 <= k < T - tau1, i.e. tau2 must be a step of the run
+    (tau2 <= T - 1) so that a fully-connecting stage exists.  The safety cap is an upper bound of
+    tau1 (Sec. 4.3), so the cap in force is cap = min(tau_cap, T - 1 - k): with it Eq. 3 holds for
+    every history, also for runs shorter than tau_cap + k + 1 steps (the 28-step schedule under
+    the printed SD3 setting tau_cap = 40).  k >= T leaves no admissible tau1: ValueError."""
     M = _f64(M)
+    T = len(M)
+    if k < 1 or k > T - 1:
+        raise ValueError("Eq. 3 needs 1 <= k < T - tau1 for some tau1 >= 0: k = %d, T = %d" % (k, T))
+    cap = min(tau_cap, T - 1 - k)
     tau1 = None
-    for i in range(L, len(M)):
+    for i in range(L, T):
         G = (M[i - L] - M[i]) / L
         if 0.0 <= G < g_slope:
-            tau1 = min(i, tau_cap)
+            tau1 = min(i, cap)
             break
     if tau1 is None:
-        tau1 = tau_cap
+        tau1 = cap
     return tau1, tau1 + k
 
 

@@ -71,6 +71,8 @@ SIGNATURES = {
     "hyb_cfg_disc_euler": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _sz, _f, _f, _f, _vp, _vp, _i, _vp, _sz, _vp]),
     "hyb_cfg_disc_affine": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _sz, _f, _f, _f, _vp, _vp, _i, _vp, _sz, _vp]),
     "hyb_joint_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp]),
+    "hyb_joint_attention_ws": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _sz, _vp]),
+    "hyb_joint_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
     "hyb_adaln_modulation": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "hyb_layernorm_modulate": (_i, [_vp, _vp, _vp, _sz, _vp, _i, _i, _i, _f, _i, _vp]),
     "hyb_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _sz, _vp]),
@@ -200,6 +202,18 @@ def hyb_joint_attention(q, k, v, o, scale=0.0):
     B, H, Nq, d = q.shape
     _check(lib().hyb_joint_attention(_p(q), _p(k, q.dtype), _p(v, q.dtype), _p(o, q.dtype), B, H, Nq, k.shape[2], d,
                                      scale, _dt(q), _stream()))
+    return o
+
+
+def hyb_joint_attention_workspace_bytes(batch, heads, n_q, dtype):
+    return lib().hyb_joint_attention_workspace_bytes(batch, heads, n_q, dtype)
+
+
+def hyb_joint_attention_ws(q, k, v, o, workspace, scale=0.0):
+    """hyb_joint_attention with scratch (torch.uint8 tensor of hyb_joint_attention_workspace_bytes, or None)."""
+    B, H, Nq, d = q.shape
+    _check(lib().hyb_joint_attention_ws(_p(q), _p(k, q.dtype), _p(v, q.dtype), _p(o, q.dtype), B, H, Nq, k.shape[2], d,
+                                        scale, _dt(q), _p(workspace), _nbytes(workspace), _stream()))
     return o
 
 

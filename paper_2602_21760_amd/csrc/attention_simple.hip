@@ -66,17 +66,44 @@ int hyb_launch_attention(const AttnArgs& a, hyb_dtype dtype, hipStream_t st) {
     return hyb_launch_attention_simple(a, dtype, st);
 }
 
-extern "C" int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
-                                   int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
-                                   hyb_dtype dtype, void* stream) {
+namespace {
+int joint_attention(const char* who, const void* q, const void* k, const void* v, void* o,
+                    int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
+                    hyb_dtype dtype, void* workspace, size_t workspace_bytes, bool with_ws, void* stream) {
     HYB_CHECK_DTYPE(dtype);
-    HYB_REQUIRE(batch >= 0 && heads >= 0 && n_q >= 0 && n_kv >= 0, HYB_ERR_SHAPE, "hyb_joint_attention: negative size");
-    HYB_REQUIRE(head_dim == 64, HYB_ERR_SHAPE, "hyb_joint_attention: head_dim %d is not supported (only 64)", head_dim);
-    HYB_REQUIRE(batch <= 65535 && heads <= 65535, HYB_ERR_SHAPE, "hyb_joint_attention: batch and heads must be at most 65535");
+    HYB_REQUIRE(batch >= 0 && heads >= 0 && n_q >= 0 && n_kv >= 0, HYB_ERR_SHAPE, "%s: negative size", who);
+    HYB_REQUIRE(head_dim == 64, HYB_ERR_SHAPE, "%s: head_dim %d is not supported (only 64)", who, head_dim);
+    HYB_REQUIRE(batch <= 65535 && heads <= 65535, HYB_ERR_SHAPE, "%s: batch and heads must be at most 65535", who);
     if (batch == 0 || heads == 0 || n_q == 0) return HYB_OK;
-    HYB_REQUIRE(n_kv > 0, HYB_ERR_SHAPE, "hyb_joint_attention: n_kv == 0 with n_q > 0 (softmax over an empty set)");
+    HYB_REQUIRE(n_kv > 0, HYB_ERR_SHAPE, "%s: n_kv == 0 with n_q > 0 (softmax over an empty set)", who);
     HYB_CHECK_PTR(q); HYB_CHECK_PTR(k); HYB_CHECK_PTR(v); HYB_CHECK_PTR(o);
     HYB_CHECK_ALIGN(q); HYB_CHECK_ALIGN(k); HYB_CHECK_ALIGN(v); HYB_CHECK_ALIGN(o);
     AttnArgs a = {q, k, v, o, nullptr, n_q, batch, heads, n_q, n_kv, scale > 0.f ? scale : 0.125f};
+    if (with_ws) {
+        const size_t need = hyb_joint_attention_workspace_bytes(batch, heads, n_q, dtype);
+        if (need > 0) {
+            HYB_CHECK_PTR(workspace); HYB_CHECK_ALIGN(workspace);
+            HYB_REQUIRE(workspace_bytes >= need, HYB_ERR_WORKSPACE, "%s: workspace of %zu bytes is smaller than the %zu required", who, workspace_bytes, need);
+            a.part = static_cast<float*>(workspace);
+        }
+    }
     return hyb_launch_attention(a, dtype, (hipStream_t)stream);
+}
+}  // namespace
+
+extern "C" int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
+                                   int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
+                                   hyb_dtype dtype, void* stream) {
+    return joint_attention("hyb_joint_attention", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, nullptr, 0, false, stream);
+}
+
+extern "C" size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dtype dtype) {
+    if (dtype != HYB_BF16 || batch <= 0 || heads <= 0 || n_q <= 0) return 0;
+    return hyb_align_up(hyb_attention_split_bytes(batch, heads, n_q), 256);
+}
+
+extern "C" int hyb_joint_attention_ws(const void* q, const void* k, const void* v, void* o,
+                                      int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
+                                      hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return joint_attention("hyb_joint_attention_ws", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, workspace, workspace_bytes, true, stream);
 }

@@ -69,6 +69,18 @@ def test_argument_validation_happens_before_any_gpu_work(lib):
     assert lib.hyb_joint_attention(vp(16), vp(16), vp(16), vp(16), 1, 1, 8, 8, 32, 0.0, 0, None) == 2   # head_dim
     assert lib.hyb_joint_attention(vp(16), vp(16), vp(16), vp(16), 1, 1, 8, 0, 64, 0.0, 0, None) == 2   # n_kv == 0
     assert lib.hyb_joint_attention(None, None, None, None, 1, 1, 0, 0, 64, 0.0, 0, None) == 0           # n_q == 0
+    # workspace form: the query is 0 for fp32 and for shapes that are never split; the cfg 2 shape (24 heads,
+    # 4429 rows: 105 query blocks per XCD on 32 CUs) wants scratch, and a short one is an error
+    lib.hyb_joint_attention_workspace_bytes.restype = sz
+    lib.hyb_joint_attention_workspace_bytes.argtypes = [i, i, i, i]
+    assert lib.hyb_joint_attention_workspace_bytes(1, 24, 4429, 0) == 0
+    assert lib.hyb_joint_attention_workspace_bytes(1, 3, 4429, 1) == 0          # pairs not a multiple of 8
+    need = lib.hyb_joint_attention_workspace_bytes(1, 24, 4429, 1)
+    assert need > 0 and need % 256 == 0
+    lib.hyb_joint_attention_ws.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    assert lib.hyb_joint_attention_ws(vp(16), vp(16), vp(16), vp(16), 1, 24, 4429, 4429, 64, 0.0, 1, vp(256), need - 1, None) == 5
+    assert lib.hyb_joint_attention_ws(vp(16), vp(16), vp(16), vp(16), 1, 24, 4429, 4429, 64, 0.0, 1, None, 0, None) == 1
+    assert lib.hyb_joint_attention_ws(None, None, None, None, 1, 1, 0, 0, 64, 0.0, 0, None, 0, None) == 0
     lib.hyb_branch_discrepancy.argtypes = [vp, vp, i, sz, i, i, vp, vp, sz, vp]
     assert lib.hyb_branch_discrepancy(vp(16), vp(16), 1, 4096, 2, 0, vp(16), vp(256), 8, None) == 5     # workspace
     assert lib.hyb_branch_discrepancy(vp(16), vp(16), 1, 4096, 3, 0, vp(16), vp(256), 1 << 20, None) == 3

@@ -6,7 +6,7 @@ import torch
 
 from oracle import hyb_oracle as O
 from paper_2602_21760_amd import synth
-from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, host, rel_l2, tdt, tol
+from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, host, err, tdt, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -48,7 +48,7 @@ def _block_case(hb, cfg, seed=0, same_rows=False, with_oracle=True):
 def test_cfg1_block_fp32(hb):
     cfg = synth.CFG1
     g_img, g_txt, r_img, r_txt, _ = _block_case(hb, cfg)
-    assert rel_l2(g_img, r_img) < TOL_F32 and rel_l2(g_txt, r_txt) < TOL_F32
+    assert err(g_img, r_img) < TOL_F32 and err(g_txt, r_txt) < TOL_F32
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
@@ -58,9 +58,9 @@ def test_block_ragged_reduced_size(hb, dt):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=36, n_txt=77, ctx_dim=128, batch=2, dtype=dt)
     assert cfg.n_img == 324
     g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=10)
-    assert rel_l2(g_img, r_img) < tol(dt) and rel_l2(g_txt, r_txt) < tol(dt)
+    assert err(g_img, r_img) < tol(dt) and err(g_txt, r_txt) < tol(dt)
     # error relative to what the block actually adds (not hidden behind the residual)
-    assert rel_l2(g_img - x_img, r_img - x_img) < (5e-2 if dt == "bf16" else 1e-3)
+    assert err(g_img - x_img, r_img - x_img) < (5e-2 if dt == "bf16" else 1e-3)
 
 
 def test_block_with_more_text_than_image_tokens(hb):
@@ -69,8 +69,8 @@ def test_block_with_more_text_than_image_tokens(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=14, n_txt=211, ctx_dim=128, batch=3, dtype="bf16")
     assert cfg.n_img == 49
     g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=21)
-    assert rel_l2(g_img, r_img) < TOL_BF16 and rel_l2(g_txt, r_txt) < TOL_BF16
-    assert rel_l2(g_img - x_img, r_img - x_img) < 5e-2
+    assert err(g_img, r_img) < TOL_BF16 and err(g_txt, r_txt) < TOL_BF16
+    assert err(g_img - x_img, r_img - x_img) < 5e-2
 
 
 def test_block_attention_with_split_tail(hb):
@@ -79,10 +79,10 @@ def test_block_attention_with_split_tail(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=142, n_txt=77, ctx_dim=128, batch=2, dtype="bf16")
     assert cfg.n_img + cfg.n_txt == 5118
     g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=31)
-    assert rel_l2(g_img, r_img) < TOL_BF16 and rel_l2(g_txt, r_txt) < TOL_BF16
-    assert rel_l2(g_img - x_img, r_img - x_img) < 5e-2
+    assert err(g_img, r_img) < TOL_BF16 and err(g_txt, r_txt) < TOL_BF16
+    assert err(g_img - x_img, r_img - x_img) < 5e-2
     # the split query blocks are the last 8 of every pair: image rows 4096 .. 5040 and the text rows
-    assert rel_l2(g_img[:, 4096:] - x_img[:, 4096:], r_img[:, 4096:] - x_img[:, 4096:]) < 5e-2
+    assert err(g_img[:, 4096:] - x_img[:, 4096:], r_img[:, 4096:] - x_img[:, 4096:]) < 5e-2
     # the merge adds the parts in a fixed order: a second run gives the same bits
     g_img2, g_txt2, _, _, _ = _block_case(hb, cfg, seed=31, with_oracle=False)
     assert np.array_equal(g_img, g_img2) and np.array_equal(g_txt, g_txt2)
@@ -99,7 +99,7 @@ def test_block_batch_invariance_and_determinism(hb):
 def test_block_without_text_and_empty_batch(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=128, heads=2, latent_hw=20, n_txt=0, ctx_dim=128, batch=1)
     g_img, g_txt, r_img, r_txt, _ = _block_case(hb, cfg, seed=30)
-    assert rel_l2(g_img, r_img) < TOL_BF16 and g_txt.shape == r_txt.shape == (1, 0, 128)
+    assert err(g_img, r_img) < TOL_BF16 and g_txt.shape == r_txt.shape == (1, 0, 128)
 
 
 def _forward_case(cfg, ctxs, t):
@@ -119,7 +119,7 @@ def test_cfg1_end_to_end_fp32(hb):
     """Tiny fp32 workload: batch 2 (cond + uncond), one Euler step t = 0.5 -> 0.45, guidance 7."""
     cfg = synth.CFG1
     m, v, ref_v, lat = _forward_case(cfg, "cu", 0.5)
-    assert rel_l2(host(v), ref_v) < TOL_F32
+    assert err(host(v), ref_v) < TOL_F32
     x = dev(lat).clone()
     n = cfg.latent_elems
     d1, d2 = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
@@ -127,8 +127,8 @@ def test_cfg1_end_to_end_fp32(hb):
     ws = torch.empty(hb.hyb_discrepancy_workspace_bytes(1, n), device="cuda", dtype=torch.uint8)
     hb.hyb_cfg_disc_euler(v[0:1], v[1:2], x.view(1, -1), x.view(1, -1), 7.0, 0.5, 0.45, d1, d2, ws, v_out=vout)
     rx, rv, r1, r2 = O.guided_step(lat[None], ref_v[0:1], ref_v[1:2], 7.0, np.float32(0.5), np.float32(0.45))
-    assert rel_l2(host(vout), rv.reshape(1, -1)) < TOL_F32
-    assert rel_l2(host(x), rx[0]) < TOL_F32
+    assert err(host(vout), rv.reshape(1, -1)) < TOL_F32
+    assert err(host(x), rx[0]) < TOL_F32
     # end-to-end discrepancy (fp32 path): oracle branches vs GPU branches
     assert abs(d1.item() - r1[0]) < TOL_DISC * r1[0] and abs(d2.item() - r2[0]) < TOL_DISC * r2[0]
     # same text in both rows -> bit-identical branches -> discrepancy exactly 0
@@ -156,7 +156,7 @@ def test_reduced_bf16_forward_and_guided_loop(hb):
     blocks = list(synth.mmdit_blocks(cfg))
     rx, M1, M2 = O.sampling_loop(lat[None], ctx_c[None], ctx_u[None], P, lambda: blocks, cfg.heads, cfg.patch, T,
                                  cfg.shift, cfg.guidance)
-    assert rel_l2(host(x), rx[0]) < TOL_BF16
+    assert err(host(x), rx[0]) < TOL_BF16
     # end-to-end discrepancies are reported against the oracle's (bf16 branch noise is comparable to the
     # branch difference for random-init weights, so only a loose check applies here)
     g1, g2 = host(gs.disc[0, :T]), host(gs.disc[1, :T])
@@ -181,7 +181,7 @@ def test_guided_loop_with_switching_controller(hb):
     blocks = list(synth.mmdit_blocks(cfg))
     rx, M1, _ = O.sampling_loop(lat[None], ctx_c[None], ctx_u[None], P, lambda: blocks, cfg.heads, cfg.patch, T,
                                 cfg.shift, cfg.guidance)
-    assert rel_l2(host(x), rx[0]) < TOL_F32 * 10          # 14 steps of accumulated fp32 rounding
+    assert err(host(x), rx[0]) < TOL_F32 * 10          # 14 steps of accumulated fp32 rounding
     g1 = host(gs.disc[0, :T])
     assert np.all(np.abs(g1 - M1[:, 0]) < TOL_DISC * M1[:, 0])
     tau1, tau2 = O.switching_points(M1[:, 0], L, g_slope, tau_cap, k)
@@ -223,7 +223,7 @@ def test_pre_only_text_stream_on_gpu(hb, dt):
     assert torch.equal(outs[True][0], outs[False][0])
     assert torch.all(outs[True][1] == 7.0) and torch.equal(outs[True][2], dev(x_txt))
     r_img, r_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads, txt_pre_only=True)
-    assert rel_l2(host(outs[True][0]), r_img) < (TOL_BF16 if dt == "bf16" else TOL_F32)
+    assert err(host(outs[True][0]), r_img) < (TOL_BF16 if dt == "bf16" else TOL_F32)
     # whole model
     P = synth.mmdit_globals(cfg)
     lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
@@ -250,6 +250,6 @@ def test_forward_with_pooled_text_conditioning(hb, dt):
     m = model.MMDiT(cfg, P, synth.mmdit_blocks(cfg))
     v = m.forward(dev(latent), dev(ctx), torch.full((2,), 0.5, device="cuda"), dev(pooled))
     ref = O.mmdit_forward(latent, ctx, np.array([0.5, 0.5]), P, synth.mmdit_blocks(cfg), cfg.heads, cfg.patch, pooled=pooled)
-    assert rel_l2(host(v), ref) < (TOL_BF16 if dt == "bf16" else TOL_F32)
+    assert err(host(v), ref) < (TOL_BF16 if dt == "bf16" else TOL_F32)
     ref0 = O.mmdit_forward(latent, ctx, np.array([0.5, 0.5]), P, synth.mmdit_blocks(cfg), cfg.heads, cfg.patch)
-    assert rel_l2(ref, ref0) > 10 * (TOL_BF16 if dt == "bf16" else TOL_F32) or dt == "bf16"   # the pooled path matters
+    assert err(ref, ref0) > 10 * (TOL_BF16 if dt == "bf16" else TOL_F32) or dt == "bf16"   # the pooled path matters

@@ -10,7 +10,7 @@ import torch
 
 from oracle import hyb_oracle as O
 from paper_2602_21760_amd import synth
-from gpu_util import TOL_BF16, TOL_DISC, dev, host, rel_l2
+from gpu_util import TOL_BF16, TOL_DISC, dev, host, err
 
 pytestmark = pytest.mark.gpu
 
@@ -31,7 +31,7 @@ def test_attention_full_size_sampled_rows(hb, shape):
     rows = np.unique(np.concatenate([[0, 1, 31, 32, 127, 128, N - 334, N - 333, N - 2, N - 1],
                                      np.random.default_rng(0).integers(0, N, 40)]))
     ref = O.attention(q, k, v, rows=rows)
-    assert rel_l2(host(o)[:, rows], ref) < 1e-2
+    assert err(host(o)[:, rows], ref) < 1e-2
 
 
 # the four GEMMs of a joint block at the batch-2 row counts (image rows; text rows ride in the same launch)
@@ -44,7 +44,7 @@ def test_linear_full_shapes_sampled_rows(hb, nk):
     hb.hyb_linear(dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(b), out, hb.HYB_EPI_GELU_TANH)
     rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, m - 78, m - 77, m - 1], np.random.default_rng(1).integers(0, m, 48)]))
     ref = O.gelu_tanh(O.linear(a[rows], w, b))
-    assert rel_l2(host(out)[rows], ref) < 1e-2
+    assert err(host(out)[rows], ref) < 1e-2
 
 
 @pytest.mark.timeout(600)
@@ -63,9 +63,9 @@ def test_guided_step_full_tokens_reduced_depth(hb):
     v_gpu = host(m.v)
     tt = np.full(2, np.float32(sig[0]))
     ref_v = O.mmdit_forward(np.stack([lat, lat]), np.stack([ctx_c, ctx_u]), tt, P, blocks, cfg.heads, cfg.patch)
-    assert rel_l2(v_gpu, ref_v) < TOL_BF16
+    assert err(v_gpu, ref_v) < TOL_BF16
     rx, _, r1, r2 = O.guided_step(lat[None], ref_v[0:1], ref_v[1:2], cfg.guidance, np.float32(sig[0]), np.float32(sig[1]))
-    assert rel_l2(host(x), rx[0]) < TOL_BF16
+    assert err(host(x), rx[0]) < TOL_BF16
     # discrepancy on IDENTICAL branch outputs (the GPU's bf16 velocities fed to both reductions)
     t1, t2 = O.branch_discrepancy(v_gpu[0:1], v_gpu[1:2], 1)[0], O.branch_discrepancy(v_gpu[0:1], v_gpu[1:2], 2)[0]
     g1, g2 = gs.disc[0, 0].item(), gs.disc[1, 0].item()
@@ -101,7 +101,7 @@ def test_cfg2_full_forward(hb, capsys):
             with capsys.disabled():
                 print("  [cfg2 full] oracle block %d / %d, %.0f s" % (i + 1, cfg.blocks, time.time() - t0), flush=True)
     ref = O.mmdit_final(x_img, temb, P, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch)
-    err = rel_l2(v, ref)
+    err = err(v, ref)
     with capsys.disabled():
         print("  [cfg2 full] rel-L2 of v vs oracle: %.3e (%.0f s)" % (err, time.time() - t0), flush=True)
     assert err < TOL_BF16
@@ -134,5 +134,5 @@ def test_block_high_resolution_sampled_rows(hb, capsys, cfg):
     with capsys.disabled():
         print("  [%s block] GPU done, oracle on %d + %d sampled rows ..." % (cfg.name, len(ri), len(rt)), flush=True)
     r_img, r_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
-    assert rel_l2(g_img[:, ri], r_img) < TOL_BF16 and rel_l2(g_txt[:, rt], r_txt) < TOL_BF16
-    assert rel_l2(g_img[:, ri] - x_img[:, ri], r_img - x_img[:, ri]) < 5e-2
+    assert err(g_img[:, ri], r_img) < TOL_BF16 and err(g_txt[:, rt], r_txt) < TOL_BF16
+    assert err(g_img[:, ri] - x_img[:, ri], r_img - x_img[:, ri]) < 5e-2

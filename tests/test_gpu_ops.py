@@ -6,7 +6,7 @@ import torch
 
 from oracle import hyb_oracle as O
 from paper_2602_21760_amd import synth
-from gpu_util import dev, host, rel_l2, tdt, tol
+from gpu_util import dev, host, err, tdt, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -39,7 +39,7 @@ def test_linear_epilogues(hb, dt, shape):
         for od in ("f32", dt):
             out = torch.empty(m, n, device="cuda", dtype=tdt(od))
             hb.hyb_linear(da, dw, db, out, epi)
-            assert rel_l2(host(out), fn(y)) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
+            assert err(host(out), fn(y)) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
     # gate * y + residual with a per-sample gate (3 "samples" of ragged size) and without gate
     rpg = (m + 2) // 3
     res, gate = _data(4, (m, n), "f32"), _data(5, (3, 2 * n), "f32")
@@ -48,13 +48,13 @@ def test_linear_epilogues(hb, dt, shape):
     hb.hyb_linear(da, dw, db, out, hb.HYB_EPI_GATE_RESIDUAL, residual=dres, gate=dgate[:, n:], rows_per_gate=rpg,
                   gate_stride=2 * n)
     g_rows = gate[np.arange(m) // rpg, n:]
-    assert rel_l2(host(out), res + g_rows * y) < tol(dt)
+    assert err(host(out), res + g_rows * y) < tol(dt)
     hb.hyb_linear(da, dw, db, dres, hb.HYB_EPI_GATE_RESIDUAL, residual=dres)     # in place, gate = 1
-    assert rel_l2(host(dres), res + y) < tol(dt)
+    assert err(host(dres), res + y) < tol(dt)
     # no bias
     out = torch.empty(m, n, device="cuda")
     hb.hyb_linear(da, dw, None, out)
-    assert rel_l2(host(out), O.linear(a, w)) < tol(dt)
+    assert err(host(out), O.linear(a, w)) < tol(dt)
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
@@ -69,10 +69,10 @@ def test_linear_geglu(hb, dt, shape):
     for od in ("f32", dt):
         out = torch.empty(m, n, device="cuda", dtype=tdt(od))
         hb.hyb_linear(da, dw, db, out, hb.HYB_EPI_GEGLU)
-        assert rel_l2(host(out), ref) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
+        assert err(host(out), ref) < (tol(dt) if od == "f32" and dt == "f32" else max(tol(dt), 4e-3))
     out = torch.empty(m, n, device="cuda", dtype=tdt(dt))
     hb.hyb_linear(da, dw, None, out, hb.HYB_EPI_GEGLU)                       # no bias
-    assert rel_l2(host(out), O.linear(a, w[:n]) * O.gelu_erf(O.linear(a, w[n:]))) < max(tol(dt), 4e-3)
+    assert err(host(out), O.linear(a, w[:n]) * O.gelu_erf(O.linear(a, w[n:]))) < max(tol(dt), 4e-3)
 
 
 def test_linear_odd_k_f32(hb):
@@ -80,7 +80,7 @@ def test_linear_odd_k_f32(hb):
     a, w, b = _data(1, (m, k), "f32"), _data(2, (n, k), "f32"), _data(3, (n,), "f32")
     out = torch.empty(m, n, device="cuda")
     hb.hyb_linear(dev(a), dev(w), dev(b), out)
-    assert rel_l2(host(out), O.linear(a, w, b)) < 1e-6
+    assert err(host(out), O.linear(a, w, b)) < 1e-6
 
 
 @pytest.mark.parametrize("od", ["f32", "bf16"])
@@ -93,9 +93,9 @@ def test_layernorm_modulate(hb, od, hidden):
     out = torch.empty(B, T, hidden, device="cuda", dtype=tdt(od))
     hb.hyb_layernorm_modulate(dx, dmod[:, hidden:], dmod[:, 2 * hidden:], 3 * hidden, out, 1e-6)
     ref = O.modulate(O.layer_norm(x, 1e-6), mod[:, hidden:2 * hidden], mod[:, 2 * hidden:])
-    assert rel_l2(host(out), ref) < (4e-3 if od == "bf16" else 1e-5)
+    assert err(host(out), ref) < (4e-3 if od == "bf16" else 1e-5)
     hb.hyb_layernorm_modulate(dx, None, None, 0, out, 1e-6)
-    assert rel_l2(host(out), O.layer_norm(x, 1e-6)) < (4e-3 if od == "bf16" else 1e-5)
+    assert err(host(out), O.layer_norm(x, 1e-6)) < (4e-3 if od == "bf16" else 1e-5)
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
@@ -106,7 +106,7 @@ def test_adaln_modulation(hb, dt, batch):
     temb = _data(22, (batch, hidden), "f32")
     out = torch.empty(batch, rows, device="cuda")
     hb.hyb_adaln_modulation(dev(w, tdt(dt)), dev(b), dev(temb), out)
-    assert rel_l2(host(out), O.linear(O.silu(temb), w, b)) < 1e-5
+    assert err(host(out), O.linear(O.silu(temb), w, b)) < 1e-5
 
 
 def test_timestep_embedding_and_patchify(hb):
@@ -142,9 +142,9 @@ def test_attention(hb, dt, shape):
     q, k, v = _data(40, (B, H, Nq, 64), dt), _data(41, (B, H, Nk, 64), dt), _data(42, (B, H, Nk, 64), dt)
     o = torch.empty(B, Nq, H * 64, device="cuda", dtype=tdt(dt))
     hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o)
-    assert rel_l2(host(o), O.attention(q, k, v)) < (tol(dt) if dt == "f32" else 1e-2)
+    assert err(host(o), O.attention(q, k, v)) < (tol(dt) if dt == "f32" else 1e-2)
     hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o, scale=0.3)
-    assert rel_l2(host(o), O.attention(q, k, v, scale=0.3)) < (tol(dt) if dt == "f32" else 1e-2)
+    assert err(host(o), O.attention(q, k, v, scale=0.3)) < (tol(dt) if dt == "f32" else 1e-2)
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
@@ -155,14 +155,14 @@ def test_attention_invariants_on_gpu(hb, dt):
     o = torch.empty(B, N, H * 64, device="cuda", dtype=tdt(dt))
     hb.hyb_joint_attention(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o)
     mean_v = np.concatenate([v[0, h].astype(np.float64).mean(0) for h in range(H)])
-    assert rel_l2(host(o)[0], np.broadcast_to(mean_v, (N, H * 64))) < (1e-5 if dt == "f32" else 1e-2)
+    assert err(host(o)[0], np.broadcast_to(mean_v, (N, H * 64))) < (1e-5 if dt == "f32" else 1e-2)
     # large logits: the streaming softmax must not overflow
     qb = _data(53, (B, H, N, 64), dt) * 6
     kb = _data(54, (B, H, N, 64), dt) * 6
     hb.hyb_joint_attention(dev(qb, tdt(dt)), dev(kb, tdt(dt)), dev(v, tdt(dt)), o)
     got = host(o)
     assert np.isfinite(got).all()
-    assert rel_l2(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 2e-2)
+    assert err(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 2e-2)
 
 
 @pytest.mark.parametrize("growth", [3.0, 7.5, 40.0])
@@ -187,4 +187,55 @@ def test_attention_running_maximum_schedules(hb, growth):
     hb.hyb_joint_attention(dev(q, torch.bfloat16), dev(k, torch.bfloat16), dev(v, torch.bfloat16), o)
     got = host(o)
     assert np.isfinite(got).all()
-    assert rel_l2(got, O.attention(q, k, v)) < 1e-2
+    assert err(got, O.attention(q, k, v)) < 1e-2
+
+
+@pytest.mark.parametrize("shape", [(1, 8, 5118, 5118), (1, 8, 700, 700), (2, 12, 4429, 4429)])
+def test_attention_with_workspace_splits_and_matches(hb, shape):
+    """hyb_joint_attention_ws: with scratch the kernel may cut overloading query blocks along the keys and merge
+    the parts; both forms against the oracle (sampled rows incl. the last query blocks, which are the ones that
+    get cut), the two forms against each other, and the split form twice for identical bits."""
+    B, H, Nq, Nk = shape
+    q, k, v = _data(140, (B, H, Nq, 64), "bf16"), _data(141, (B, H, Nk, 64), "bf16"), _data(142, (B, H, Nk, 64), "bf16")
+    dq, dk, dv = (dev(a, torch.bfloat16) for a in (q, k, v))
+    need = hb.hyb_joint_attention_workspace_bytes(B, H, Nq, hb.HYB_BF16)
+    assert (need > 0) == (Nq != 700)                  # 6 query blocks per XCD never overload a CU
+    ws = torch.empty(max(need, 256), device="cuda", dtype=torch.uint8)
+    o_ws, o_ws2, o_plain = (torch.empty(B, Nq, H * 64, device="cuda", dtype=torch.bfloat16) for _ in range(3))
+    hb.hyb_joint_attention_ws(dq, dk, dv, o_ws, ws)
+    ws.fill_(0xFF)                                    # contents of the scratch are irrelevant on entry
+    hb.hyb_joint_attention_ws(dq, dk, dv, o_ws2, ws)
+    hb.hyb_joint_attention(dq, dk, dv, o_plain)
+    assert torch.equal(o_ws, o_ws2)
+    rows = np.unique(np.concatenate([np.arange(Nq - 200, Nq), [0, 1, 127, 128], np.random.default_rng(3).integers(0, Nq, 60)]))
+    ref = O.attention(q, k, v, rows=rows)
+    assert err(host(o_ws)[:, rows], ref) < 1e-2 and err(host(o_plain)[:, rows], ref) < 1e-2
+    assert err(host(o_ws), host(o_plain)) < 1e-2      # every row of the two forms (bf16 output rounding apart)
+    if need == 0:
+        assert torch.equal(o_ws, o_plain)
+    if need:
+        with pytest.raises(hb.HybError):
+            hb.hyb_joint_attention_ws(dq, dk, dv, o_ws, ws[:need - 256])
+
+
+def test_workload_gemms_take_the_mfma_path(hb):
+    """Every bf16 GEMM shape of the SD3-shaped and SDXL-shaped workloads (k % 64 == 0, n % 8 == 0) is served by
+    the MFMA kernel: the library's launch trace names the kernel each call ran, and none is the plain FMA one."""
+    shapes = {(4608, 1536), (1536, 1536), (6144, 1536), (1536, 6144), (1536, 64), (1536, 4096), (64, 1536),
+              (1536, 256),                                                        # SD3-shaped branch incl. embed / final
+              (1920, 640), (640, 640), (1280, 2048), (5120, 640), (640, 2560),   # SDXL stage A
+              (3840, 1280), (1280, 1280), (2560, 2048), (10240, 1280), (1280, 5120)}   # stage B
+    hb.hyb_trace_enable(True)
+    try:
+        for n, k in sorted(shapes):
+            for m in (1, 77, 333, 1024):
+                a = torch.zeros(m, k, device="cuda", dtype=torch.bfloat16)
+                w = torch.zeros(n, k, device="cuda", dtype=torch.bfloat16)
+                out = torch.empty(m, n, device="cuda", dtype=torch.bfloat16)
+                hb.hyb_linear(a, w, None, out)
+        torch.cuda.synchronize()
+        names = hb.hyb_trace_summary()
+    finally:
+        hb.hyb_trace_enable(False)
+    assert names and all(nm.startswith(("gemm_mfma", "gemm_splitk")) for nm in names), sorted(names)
+    assert sum(r["launches"] for nm, r in names.items() if nm.startswith("gemm_mfma")) == len(shapes) * 4

@@ -7,7 +7,7 @@ import torch
 
 from oracle import hyb_oracle as O
 from paper_2602_21760_amd import synth
-from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, host, rel_l2, tdt, tol
+from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, host, err, tdt, tol
 
 pytestmark = pytest.mark.gpu
 
@@ -28,9 +28,9 @@ def test_groupnorm(hb, shape):
     ws = torch.empty(hb.hyb_groupnorm_workspace_bytes(B, 32), device="cuda", dtype=torch.uint8)
     dx = dev(x)
     hb.hyb_groupnorm(dx, dev(g), dev(b), out, 32, 1e-5, ws)
-    assert rel_l2(host(out), O.group_norm(x, 32, g, b, 1e-5)) < 1e-5
+    assert err(host(out), O.group_norm(x, 32, g, b, 1e-5)) < 1e-5
     hb.hyb_groupnorm(dx, dev(g), dev(b), dx, 32, 1e-5, ws)          # in place
-    assert rel_l2(host(dx), O.group_norm(x, 32, g, b, 1e-5)) < 1e-5
+    assert err(host(dx), O.group_norm(x, 32, g, b, 1e-5)) < 1e-5
 
 
 @pytest.mark.parametrize("od", ["f32", "bf16"])
@@ -39,7 +39,7 @@ def test_layernorm_affine(hb, od):
     g, b = synth.normal(84, (640,), 0.1, "f32", mean=1.0), synth.normal(85, (640,), 0.1, "f32")
     out = torch.empty(2, 33, 640, device="cuda", dtype=tdt(od))
     hb.hyb_layernorm_affine(dev(x), dev(g), dev(b), out, 1e-5)
-    assert rel_l2(host(out), O.layer_norm_affine(x, g, b, 1e-5)) < (4e-3 if od == "bf16" else 1e-5)
+    assert err(host(out), O.layer_norm_affine(x, g, b, 1e-5)) < (4e-3 if od == "bf16" else 1e-5)
 
 
 def _stage_case(cfg, nblocks, scale_w=1.0):
@@ -67,8 +67,8 @@ def test_sdxl_block_reduced(hb, dt):
     # every sub-layer changes the stream noticeably
     cfg = synth.SDXLStageConfig("t", blocks=2, tokens=333, channels=256, heads=4, n_ctx=77, ctx_dim=128, batch=2, dtype=dt)
     got, ref, x = _stage_case(cfg, 2, scale_w=4.0)
-    assert rel_l2(got, ref) < tol(dt)
-    assert rel_l2(got - x, ref - x) < (3e-2 if dt == "bf16" else 1e-3)
+    assert err(got, ref) < tol(dt)
+    assert err(got - x, ref - x) < (3e-2 if dt == "bf16" else 1e-3)
 
 
 @pytest.mark.timeout(600)
@@ -76,8 +76,8 @@ def test_sdxl_block_reduced(hb, dt):
 def test_sdxl_stage_real_shapes_one_block(hb, stage):
     cfg = synth.CFG5A if stage == "A" else synth.CFG5B
     got, ref, x = _stage_case(cfg, 1)
-    assert rel_l2(got, ref) < TOL_BF16
-    assert rel_l2(got - x, ref - x) < 5e-2
+    assert err(got, ref) < TOL_BF16
+    assert err(got - x, ref - x) < 5e-2
 
 
 def test_sdxl_block_is_deterministic_with_split_k(hb):
@@ -111,8 +111,8 @@ def test_sdxl_stage_2048_shapes_sampled_rows(hb, stage):
     rows = np.unique(np.concatenate([[0, 127, 128, cfg.tokens - 1], np.random.default_rng(6).integers(0, cfg.tokens, 44)]))
     ref = O.sdxl_block_rows(x, ctx, w, cfg.heads, rows)
     got = host(dx)[:, rows]
-    assert rel_l2(got, ref) < TOL_BF16
-    assert rel_l2(got - x[:, rows], ref - x[:, rows]) < 5e-2
+    assert err(got, ref) < TOL_BF16
+    assert err(got - x[:, rows], ref - x[:, rows]) < 5e-2
 
 
 def test_sdxl_guidance_step(hb):
@@ -126,5 +126,5 @@ def test_sdxl_guidance_step(hb):
     d1, d2 = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
     ws = torch.empty(hb.hyb_discrepancy_workspace_bytes(1, n), device="cuda", dtype=torch.uint8)
     hb.hyb_cfg_disc_euler(dev(e_c, torch.bfloat16), dev(e_u, torch.bfloat16), dx, dx, synth.CFG5_GUIDANCE, sig, sig_next, d1, d2, ws)
-    assert rel_l2(host(dx), rx) < 1e-6
+    assert err(host(dx), rx) < 1e-6
     assert abs(d1.item() - r1[0]) < TOL_DISC * r1[0] and abs(d2.item() - r2[0]) < TOL_DISC * r2[0]

@@ -162,6 +162,42 @@ def test_forward_shapes_and_final_layer_special_case():
     np.testing.assert_array_equal(v[0], v[1])
 
 
+def test_final_layer_with_modulation_against_library_assembly():
+    """The final adaLN layer with non-zero modulation: (shift, scale) = the two halves, in that order, of
+    W_f_ada SiLU(temb) + b; y = LN(x)(1 + scale) + shift; v = unpatchify(W_f y + b_f).  Weights scaled up so that
+    a swapped (shift, scale), a dropped `1 +` or a missing SiLU would each move the result far beyond the bound;
+    the three mistakes are planted into a torch variant below to show that the pin separates them."""
+    cfg = _tiny_cfg(blocks=1)
+    P = {n: a * 10 for n, a in synth.mmdit_globals(cfg).items()}
+    rng = np.random.default_rng(7)
+    x_img = rng.standard_normal((cfg.batch, cfg.n_img, cfg.hidden))
+    temb = rng.standard_normal((cfg.batch, cfg.hidden))
+    v = O.mmdit_final(x_img, temb, P, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch)
+
+    def assemble(swap=False, plus_one=True, act=True):
+        e = F.silu(T(temb)) if act else T(temb)
+        m = F.linear(e, T(P["f_ada_w"]), T(P["f_ada_b"]))
+        a, b = m.chunk(2, dim=-1)
+        shift, scale = (b, a) if swap else (a, b)
+        y = F.layer_norm(T(x_img), (cfg.hidden,), eps=1e-6) * ((1 if plus_one else 0) + scale[:, None]) + shift[:, None]
+        tok = F.linear(y, T(P["f_w"]), T(P["f_b"])).numpy()
+        # unpatchify written out with explicit loops: token (gy, gx), patch vector ordered (dy, dx, c)
+        B, p, G = cfg.batch, cfg.patch, cfg.latent_hw // cfg.patch
+        out = np.empty((B, cfg.latent_hw, cfg.latent_hw, cfg.latent_c))
+        for b_ in range(B):
+            for gy in range(G):
+                for gx in range(G):
+                    vec = tok[b_, gy * G + gx].reshape(p, p, cfg.latent_c)
+                    out[b_, gy * p:(gy + 1) * p, gx * p:(gx + 1) * p] = vec
+        return out
+
+    ref = assemble()
+    np.testing.assert_allclose(v, ref, rtol=1e-10, atol=1e-12)
+    scale_ref = np.abs(ref).max()
+    for wrong in (dict(swap=True), dict(plus_one=False), dict(act=False)):
+        assert np.abs(assemble(**wrong) - ref).max() > 1e-2 * scale_ref
+
+
 def test_forward_depends_on_time_and_text():
     cfg = _tiny_cfg(blocks=2)
     P = {n: a * 10 for n, a in synth.mmdit_globals(cfg).items()}

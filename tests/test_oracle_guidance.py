@@ -167,3 +167,33 @@ def test_switching_rule_fires_at_plateau_and_caps():
     assert O.switching_points(np.linspace(1.0, 0.0, 40), 4, 1e-3, 20, 7) == (20, 27)
     # a rising window (negative decline) does not fire either
     assert O.switching_points(np.linspace(0.0, 1.0, 40), 4, 1e-3, 9, 2) == (9, 11)
+
+
+def test_switching_rule_keeps_eq3_bound_on_short_runs():
+    """Eq. 3: 1 <= k < T - tau1, so tau2 = tau1 + k is a step of the run.  With the printed SD3 setting
+    (L 15, g 1e-4, k 5, tau_cap 40) on a 28-step schedule the cap in force is min(40, 28 - 1 - 5) = 22.
+    Expected values are worked by hand from the rule, not computed by the oracle."""
+    L, g, k, cap, _ = _hparams()["SD3"]
+    T = 28
+    # never fires (falls by 1/27 per step, far above g): tau1 = 22, tau2 = 27 = T - 1
+    assert O.switching_points(np.linspace(1.0, 0.0, T), L, g, cap, k) == (22, 27)
+    # rising curve (negative decline) never fires either
+    assert O.switching_points(np.linspace(0.0, 1.0, T), L, g, cap, k) == (22, 27)
+    # flat from step 2 on: M[2] = M[17], the window of step 17 = 2 + L is the first flat one
+    M = np.concatenate([[1.0, 0.5], np.full(T - 2, 0.1)])
+    assert O.switching_points(M, L, g, cap, k) == (17, 22)
+    # flat from step 10 on: the test fires at step 25, beyond the cap in force -> (22, 27)
+    M = np.concatenate([np.linspace(1.0, 0.2, 10), np.full(T - 10, 0.1)])
+    assert O.switching_points(M, L, g, cap, k) == (22, 27)
+    # every (tau1, tau2) the rule can return obeys the bound of Eq. 3, whatever the history
+    rng = np.random.default_rng(5)
+    for T2 in (7, 16, 28, 46, 50):
+        for _ in range(50):
+            M = np.abs(rng.standard_normal(T2)) * rng.choice([1e-5, 1e-2, 1.0])
+            t1, t2 = O.switching_points(M, min(L, T2 - 1), g, cap, k)
+            assert 0 <= t1 <= min(cap, T2 - 1 - k) and t2 == t1 + k and 1 <= k < T2 - t1
+    # no tau1 >= 0 satisfies k < T - tau1 when k >= T
+    with pytest.raises(ValueError):
+        O.switching_points(np.ones(5), 2, g, cap, 5)
+    # on the 50-step runs of the paper the printed caps are in force unchanged (15 <= 44, 40 <= 44)
+    assert O.switching_points(np.linspace(1.0, 0.0, 50), L, g, cap, k) == (40, 45)
