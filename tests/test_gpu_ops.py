@@ -157,12 +157,13 @@ def test_attention_invariants_on_gpu(hb, dt):
     mean_v = np.concatenate([v[0, h].astype(np.float64).mean(0) for h in range(H)])
     assert err(host(o)[0], np.broadcast_to(mean_v, (N, H * 64))) < (1e-5 if dt == "f32" else 1e-2)
     # large logits: the streaming softmax must not overflow
-    qb = _data(53, (B, H, N, 64), dt) * 6
-    kb = _data(54, (B, H, N, 64), dt) * 6
+    # (scaled by a power of two: the scaled values stay bf16-representable, so both sides see the same data)
+    qb = _data(53, (B, H, N, 64), dt) * 8
+    kb = _data(54, (B, H, N, 64), dt) * 4
     hb.hyb_joint_attention(dev(qb, tdt(dt)), dev(kb, tdt(dt)), dev(v, tdt(dt)), o)
     got = host(o)
     assert np.isfinite(got).all()
-    assert err(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 2e-2)
+    assert err(got, O.attention(qb, kb, v)) < (1e-4 if dt == "f32" else 1e-2)
 
 
 @pytest.mark.parametrize("growth", [3.0, 7.5, 40.0])
