@@ -107,6 +107,20 @@ int hyb_cfg_disc_affine(const void* v_c, const void* v_u, const float* x, float*
                         float scale, float a, float b, float* disc_l1, float* disc_l2,
                         hyb_dtype v_dtype, void* workspace, size_t workspace_bytes, void* stream);
 
+/* hyb_cfg_disc_euler for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments minus the
+ * workspace, same kernels, same results bit for bit; the per-workgroup partial sums go to a device array
+ * built into the library (HYB_STATIC_SCRATCH_BYTES, held once per GPU for the life of the process).  The call
+ * allocates and frees nothing.  Sizes whose partial sums do not fit -- hyb_discrepancy_workspace_bytes(batch,
+ * n_per_sample) > HYB_STATIC_SCRATCH_BYTES, i.e. more than 32768 chunks of 256 elements over all samples --
+ * are HYB_ERR_WORKSPACE (without discrepancy outputs no scratch is used and any size is accepted).  All calls
+ * on one GPU share the array: calls that overlap in time on the same GPU (different streams) race on it. */
+#define HYB_STATIC_SCRATCH_BYTES (1 << 20)
+int hyb_cfg_disc_euler_noalloc(const void* v_c, const void* v_u, const float* x, float* x_out,
+                               void* x_out_lowp, void* v_out, int batch, size_t n_per_sample,
+                               float scale, float t, float t_next, float* disc_l1, float* disc_l2,
+                               hyb_dtype v_dtype, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Denoiser f_theta(x_t, c, t) of one guidance branch (Sec. 4.1): building blocks.
  * The paper treats f_theta as a black box; the block below is the joint image+text

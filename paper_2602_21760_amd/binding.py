@@ -70,6 +70,7 @@ SIGNATURES = {
     "hyb_euler_step": (_i, [_vp, _vp, _vp, _sz, _f, _f, _i, _i, _vp]),
     "hyb_cfg_disc_euler": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _sz, _f, _f, _f, _vp, _vp, _i, _vp, _sz, _vp]),
     "hyb_cfg_disc_affine": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _sz, _f, _f, _f, _vp, _vp, _i, _vp, _sz, _vp]),
+    "hyb_cfg_disc_euler_noalloc": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _i, _sz, _f, _f, _f, _vp, _vp, _i, _vp]),
     "hyb_joint_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp]),
     "hyb_joint_attention_ws": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _sz, _vp]),
     "hyb_joint_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
@@ -183,6 +184,17 @@ def hyb_cfg_disc_euler(v_c, v_u, x, x_out, scale, t, t_next, disc_l1=None, disc_
                                     _p(x_out_lowp, torch.bfloat16), _p(v_out, v_c.dtype), batch, n, scale, t, t_next,
                                     _p(disc_l1, torch.float32), _p(disc_l2, torch.float32), _dt(v_c),
                                     _p(workspace), _nbytes(workspace), _stream()))
+    return x_out
+
+
+def hyb_cfg_disc_euler_noalloc(v_c, v_u, x, x_out, scale, t, t_next, disc_l1=None, disc_l2=None, x_out_lowp=None,
+                               v_out=None):
+    batch = v_c.shape[0]
+    n = v_c.numel() // batch if batch else 0
+    _check(lib().hyb_cfg_disc_euler_noalloc(_p(v_c), _p(v_u, v_c.dtype), _p(x, torch.float32), _p(x_out, torch.float32),
+                                            _p(x_out_lowp, torch.bfloat16), _p(v_out, v_c.dtype), batch, n, scale, t,
+                                            t_next, _p(disc_l1, torch.float32), _p(disc_l2, torch.float32), _dt(v_c),
+                                            _stream()))
     return x_out
 
 

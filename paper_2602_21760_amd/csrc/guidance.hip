@@ -9,6 +9,14 @@
 // deterministic and independent of the batch index (no atomics anywhere).
 #include "common.h"
 
+#include <mutex>
+
+// Scratch of the allocation-free entry point (hyb_cfg_disc_euler_noalloc): the per-workgroup partial sums live in
+// this file-scope device array instead of a caller-provided workspace.  Every GPU the library runs on holds its
+// own copy until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels get
+// the device address obtained from it.
+static __device__ __align__(256) unsigned char scratch[HYB_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -273,4 +281,53 @@ extern "C" int hyb_cfg_disc_euler(const void* v_c, const void* v_u, const float*
                                   hyb_dtype v_dtype, void* workspace, size_t workspace_bytes, void* stream) {
     return hyb_cfg_disc_affine(v_c, v_u, x, x_out, x_out_lowp, v_out, batch, n_per_sample, scale, 1.0f,
                                t_next - t, disc_l1, disc_l2, v_dtype, workspace, workspace_bytes, stream);
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mx;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, looked up once per device
+
+// Address of the static scratch array on the current device (nullptr + error set on failure).
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        hyb_set_error(HYB_ERR_LAUNCH, "hyb_cfg_disc_euler_noalloc: no current device (or device index >= %d)", kMaxDevices);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lk(g_scratch_mx);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            hyb_set_error(HYB_ERR_LAUNCH, "hyb_cfg_disc_euler_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int hyb_cfg_disc_euler_noalloc(const void* v_c, const void* v_u, const float* x, float* x_out,
+                                          void* x_out_lowp, void* v_out, int batch, size_t n_per_sample,
+                                          float scale, float t, float t_next, float* disc_l1, float* disc_l2,
+                                          hyb_dtype v_dtype, void* stream) {
+    HYB_REQUIRE(batch >= 0, HYB_ERR_SHAPE, "hyb_cfg_disc_euler_noalloc: negative batch");
+    void* ws = nullptr;
+    size_t need = 0;
+    if (batch > 0 && n_per_sample > 0 && (disc_l1 || disc_l2)) {
+        // size check in integers first (the workspace query itself would overflow an int for absurd sizes)
+        HYB_REQUIRE(n_per_sample / kThreads < (size_t)HYB_STATIC_SCRATCH_BYTES, HYB_ERR_WORKSPACE,
+                    "hyb_cfg_disc_euler_noalloc: n_per_sample %zu is beyond the static scratch", n_per_sample);
+        need = hyb_discrepancy_workspace_bytes(batch, n_per_sample);
+        HYB_REQUIRE(need <= (size_t)HYB_STATIC_SCRATCH_BYTES, HYB_ERR_WORKSPACE,
+                    "hyb_cfg_disc_euler_noalloc: batch %d x %zu elements needs %zu bytes of partial sums, the static scratch holds %d "
+                    "(use hyb_cfg_disc_euler with a workspace)", batch, n_per_sample, need, HYB_STATIC_SCRATCH_BYTES);
+        ws = static_scratch();
+        if (!ws) return HYB_ERR_LAUNCH;
+    }
+    // Every partial the finalisation reads is written by this call's first kernel, so nothing has to be cleared.
+    return hyb_cfg_disc_affine(v_c, v_u, x, x_out, x_out_lowp, v_out, batch, n_per_sample, scale, 1.0f, t_next - t,
+                               disc_l1, disc_l2, v_dtype, ws, need, stream);
 }
