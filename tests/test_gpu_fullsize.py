@@ -136,3 +136,99 @@ def test_block_high_resolution_sampled_rows(hb, capsys, cfg):
     r_img, r_txt = O.mmdit_block_rows(x_img, x_txt, temb, w, cfg.heads, ri, rt)
     assert err(g_img[:, ri], r_img) < TOL_BF16 and err(g_txt[:, rt], r_txt) < TOL_BF16
     assert err(g_img[:, ri] - x_img[:, ri], r_img - x_img[:, ri]) < 5e-2
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_two_block_forward_full_oracle(hb, capsys):
+    """The 2048 x 2048 branch (16384 + 333 tokens, hidden 1536, batch 1) through embedding, TWO chained joint blocks and
+    the final layer, every output element against the full fp64 oracle (about 5 TFLOP of fp64 work)."""
+    from paper_2602_21760_amd import model
+    cfg = synth.scaled(synth.CFG4, blocks=2)
+    P = synth.mmdit_globals(cfg)
+    blocks = list(synth.mmdit_blocks(cfg))
+    lat, ctx_c, _ = synth.mmdit_inputs(cfg)
+    tt = np.full(1, 0.5, dtype=np.float32)
+    t0 = time.time()
+    m = model.MMDiT(cfg, P, blocks)
+    v = host(m.forward(dev(lat[None]), dev(ctx_c[None]), dev(tt)))
+    x_img_gpu = host(m.x_img)
+    del m
+    torch.cuda.empty_cache()
+    with capsys.disabled():
+        print("  [cfg4 2 blocks] GPU done, oracle running ...", flush=True)
+    x_img, x_txt, temb = O.mmdit_embed(lat[None], ctx_c[None], tt, P, cfg.patch)
+    for i, w in enumerate(blocks):
+        x_img, x_txt = O.mmdit_block(x_img, x_txt, temb, w, cfg.heads)
+        with capsys.disabled():
+            print("  [cfg4 2 blocks] oracle block %d / 2, %.0f s" % (i + 1, time.time() - t0), flush=True)
+    ref = O.mmdit_final(x_img, temb, P, cfg.latent_hw, cfg.latent_hw, cfg.latent_c, cfg.patch)
+    with capsys.disabled():
+        print("  [cfg4 2 blocks] v: rel-L2 %.3e, worst line %.3e; image stream after block 2: rel-L2 %.3e, worst token %.3e"
+              % (rel_l2(v, ref), worst_row(v, ref), rel_l2(x_img_gpu, x_img), worst_row(x_img_gpu, x_img)), flush=True)
+    assert err(v, ref) < TOL_BF16
+    assert err(x_img_gpu, x_img) < TOL_BF16        # every one of the 16384 token rows of the residual stream
+
+
+@pytest.mark.timeout(900)
+def test_cfg3_full_schedule_at_full_token_count(hb, capsys):
+    """The whole 28-step shifted schedule (shift 3, guidance 7) of the guided loop at 4096 + 333 tokens and hidden
+    1536, both branches batched, on a ONE-block model, with the switching controller fed online.
+    EVERY step: the fused pass is checked teacher-forced against the oracle on the GPU's own branch velocities
+    (CFG + Euler update of the latent the GPU held before the step; both discrepancies to 1e-3), and the
+    controller's stages against the oracle's rule.  The denoiser itself is checked
+    teacher-forced at sampled steps (first, middle, last): the oracle evaluates both branches on the GPU's latent of
+    that step.  The first two steps are also compared free-running (oracle loop from the initial latent)."""
+    from paper_2602_21760_amd import model
+    cfg = synth.scaled(synth.CFG3, blocks=1)
+    T = cfg.steps
+    assert T == 28 and cfg.n_img + cfg.n_txt == 4429
+    P = synth.mmdit_globals(cfg)
+    blocks = list(synth.mmdit_blocks(cfg))
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    m = model.MMDiT(cfg, P, blocks)
+    gs = model.GuidedSampler(m, cfg.guidance)
+    sig = O.sigma_schedule(T, cfg.shift)
+    L, g_slope, tau_cap, k = 15, 0.1e-3, 40, 5          # the printed SD3 setting; 28 < tau_cap: cap in force 22
+    st = hb.hyb_switch_init(T, L, g_slope, tau_cap, k)
+    ctx2 = dev(np.stack([ctx_c, ctx_u]))
+    x = dev(lat).clone()
+    xs, vs, stages = [host(x)], [], []
+    t0 = time.time()
+    for i in range(T):
+        gs.step(x, ctx2, float(sig[i]), float(sig[i + 1]), i)
+        stages.append(hb.hyb_switch_push(st, float(gs.disc[0, i].item())))
+        xs.append(host(x))
+        vs.append(host(m.v))
+    g1, g2 = host(gs.disc[0, :T]), host(gs.disc[1, :T])
+    with capsys.disabled():
+        print("  [cfg3 28 steps] GPU loop done (%.0f s); rel-L1 discrepancy first / min / last: %.4f / %.4f / %.4f" %
+              (time.time() - t0, g1[0], g1.min(), g1[-1]), flush=True)
+    # every step, teacher-forced on the GPU's velocities
+    M1 = np.empty(T)
+    for i in range(T):
+        v_c, v_u = vs[i][0:1], vs[i][1:2]
+        rx, _, r1, r2 = O.guided_step(xs[i][None], v_c, v_u, cfg.guidance, np.float32(sig[i]), np.float32(sig[i + 1]))
+        assert err(xs[i + 1], rx[0]) < 1e-6, i
+        assert abs(g1[i] - r1[0]) < TOL_DISC * r1[0] and abs(g2[i] - r2[0]) < TOL_DISC * r2[0], i
+        M1[i] = r1[0]
+    # the rule on the very values the controller was fed (they match the oracle's M1 to 1e-3, asserted above)
+    tau1, tau2 = O.switching_points(g1.astype(np.float32), L, np.float32(g_slope), tau_cap, k)
+    assert (st.tau1, st.tau2) == (tau1, tau2) and tau2 <= T - 1
+    assert stages == [O.stage_of(i, tau1, tau2) for i in range(T)]
+    # the denoiser at sampled steps, teacher-forced on the GPU's latent of that step
+    for i in (0, T // 2, T - 1):
+        tt = np.full(2, np.float32(sig[i]))
+        x_in = synth.round_bf16(xs[i].astype(np.float32))      # the branches see the bf16 copy of the fp32 latent
+        ref_v = O.mmdit_forward(np.stack([x_in, x_in]), np.stack([ctx_c, ctx_u]), tt, P, blocks, cfg.heads, cfg.patch)
+        with capsys.disabled():
+            print("  [cfg3 28 steps] step %2d: v rel-L2 %.3e, worst line %.3e (%.0f s)" %
+                  (i, rel_l2(vs[i], ref_v), worst_row(vs[i], ref_v), time.time() - t0), flush=True)
+        assert err(vs[i], ref_v) < TOL_BF16, i
+    # two steps free-running from the initial latent
+    xr = lat[None].astype(np.float64)
+    for i in range(2):
+        tt = np.full(1, sig[i])
+        v_c = O.mmdit_forward(xr, ctx_c[None], tt, P, blocks, cfg.heads, cfg.patch)
+        v_u = O.mmdit_forward(xr, ctx_u[None], tt, P, blocks, cfg.heads, cfg.patch)
+        xr, _, _, _ = O.guided_step(xr, v_c, v_u, cfg.guidance, sig[i], sig[i + 1])
+        assert err(xs[i + 1], xr[0]) < TOL_BF16, i

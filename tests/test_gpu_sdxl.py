@@ -7,7 +7,7 @@ import torch
 
 from oracle import hyb_oracle as O
 from paper_2602_21760_amd import synth
-from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, host, err, tdt, tol
+from gpu_util import TOL_BF16, TOL_DISC, TOL_F32, dev, err, host, rel_l2, tdt, tol, worst_row
 
 pytestmark = pytest.mark.gpu
 
@@ -76,6 +76,22 @@ def test_sdxl_block_reduced(hb, dt):
 def test_sdxl_stage_real_shapes_one_block(hb, stage):
     cfg = synth.CFG5A if stage == "A" else synth.CFG5B
     got, ref, x = _stage_case(cfg, 1)
+    assert err(got, ref) < TOL_BF16
+    assert err(got - x, ref - x) < 5e-2
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("stage", ["A", "B"])
+def test_sdxl_stage_real_shapes_whole_chain(hb, capsys, stage):
+    """The whole stage at its real shape: all 10 blocks on 4096 tokens x 640 channels / all 20 blocks on 1024 tokens x
+    1280 channels, batch 2, chained in place, every output element against the fp64 oracle's chain."""
+    import time
+    cfg = synth.CFG5A if stage == "A" else synth.CFG5B
+    t0 = time.time()
+    got, ref, x = _stage_case(cfg, cfg.blocks)
+    with capsys.disabled():
+        print("  [sdxl stage %s, %d blocks] rel-L2 %.3e, worst row %.3e (%.0f s)" %
+              (stage, cfg.blocks, rel_l2(got, ref), worst_row(got, ref), time.time() - t0), flush=True)
     assert err(got, ref) < TOL_BF16
     assert err(got - x, ref - x) < 5e-2
 
