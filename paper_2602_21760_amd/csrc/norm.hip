@@ -109,15 +109,20 @@ __global__ __launch_bounds__(256) void layernorm_kernel(LnArgs a) {
 constexpr int kAdaMaxBatch = 4;
 constexpr int kAdaRowsPerWave = 4;
 
+// (the weights are streamed once per call: non-temporal loads, which do not displace what the caches hold)
 template <typename WT> __device__ __forceinline__ void load8(const WT* p, float* r);
 template <> __device__ __forceinline__ void load8<float>(const float* p, float* r) {
-    const f32x4 a = *reinterpret_cast<const f32x4*>(p), b = *reinterpret_cast<const f32x4*>(p + 4);
+    const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+    const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + 4));
     r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3]; r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
 }
 template <> __device__ __forceinline__ void load8<bf16_t>(const bf16_t* p, float* r) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
+    const u32x4 a = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));   // bf16 -> fp32: the bits, shifted up
 #pragma unroll
-    for (int i = 0; i < 8; i++) r[i] = (float)a[i];
+    for (int i = 0; i < 4; i++) {
+        r[2 * i] = __uint_as_float(a[i] << 16);
+        r[2 * i + 1] = __uint_as_float(a[i] & 0xffff0000u);
+    }
 }
 
 template <typename WT>
