@@ -19,14 +19,23 @@ if ROOT not in sys.path:
 METRIC = "ms per denoiser step + TFLOP/s (MFMA %), SD3-shaped MMDiT branch at 1024²"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
-SPEC_SCLK_GHZ = 2.4           # clock of the spec-sheet peak
-SUSTAINED_SCLK_GHZ = 2.08     # what the driver reports while this benchmark runs (not measured here)
-# HBM-side bytes per launch from the rocprofv3 PMC runs recorded in profiles/pmc_hbm_traffic_cfg2_kernels.md
-# (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00, the factors a plain 1 GiB copy gives on this counter set)
-TRAFFIC_BYTES = {"attention_mfma": 70.6e6,   # inside a block: kernel 62.1 MB + merge of its split tail 8.5 MB
-                 "guidance_pass": 806.4e6,
-                 "gemm_mfma_128x128.epi4.n4608.k1536": 241.5e6, "gemm_mfma_128x128.epi1.n6144.k1536": 244.3e6,
-                 "gemm_mfma_128x128.epi3.n1536.k6144": 392.0e6}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "pmc_hbm_traffic_cfg2_kernels.md")
+
+
+def traffic_bytes():
+    """HBM-side bytes per launch of the main kernels, from the counter summary under profiles/ (two rocprofv3 --pmc
+    runs, FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a plain copy of known size): the
+    summary ends with lines `traffic_bytes <kernel name of the launch trace> <bytes>`.  Missing file: no figures."""
+    out = {}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes":
+                    out[parts[1]] = float(parts[2])
+    except OSError:
+        pass
+    return out
 
 
 CPU_BASELINE_BLOCKS = 4
@@ -57,17 +66,17 @@ def cpu_baseline(cfg, synth):
             "ms_per_step_extrapolated": dt * 1e3 * cfg.blocks / CPU_BASELINE_BLOCKS}
 
 
-def guidance_roofline(hb, torch, steps):
+def guidance_roofline(hb, torch, steps, real_shapes=True):
     """The fused CFG + discrepancy + Euler pass at its bandwidth-bound shape: 256 samples of 262144
     latent elements (bf16 velocities, fp32 latent: 12 bytes per element, 805 MB per launch)."""
     batch, n = 256, 262144
     v_c = torch.randn(batch, n, device="cuda").to(torch.bfloat16)
     v_u = torch.randn(batch, n, device="cuda").to(torch.bfloat16)
     x = torch.randn(batch, n, device="cuda")
-    xo = torch.empty_like(x)
+    xo = x     # the latent is updated in place, as the sampler does (GuidedSampler.step)
     d1, d2 = torch.empty(batch, device="cuda"), torch.empty(batch, device="cuda")
     ws = torch.empty(hb.hyb_discrepancy_workspace_bytes(batch, n), device="cuda", dtype=torch.uint8)
-    for _ in range(3):
+    for _ in range(10):
         hb.hyb_cfg_disc_euler(v_c, v_u, x, xo, 7.0, 0.5, 0.45, d1, d2, ws)
     torch.cuda.synchronize()
     hb.hyb_trace_enable(True)
@@ -80,8 +89,10 @@ def guidance_roofline(hb, torch, steps):
     gbs = tr["work"] / tr["launches"] / (us * 1e-6) / 1e9
     out = {"kernel": "guidance_pass", "shape": "batch 256 x 262144 elements", "bound": "hbm", "achieved": gbs,
            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "us_per_launch": us,
-           "bytes_per_element": 12, "traffic": TRAFFIC_BYTES["guidance_pass"],
+           "bytes_per_element": 12, "traffic": traffic_bytes().get("guidance_pass"),
            "algorithmic_bytes": tr["work"] / tr["launches"]}
+    if not real_shapes:
+        return out
     # real latent shapes (latency-bound): time in microseconds
     real = {}
     for name, ne in (("sd3_1024", 262144), ("sd3_2048", 1048576), ("sdxl_1024", 65536)):
@@ -176,9 +187,13 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--secondary", action="store_true",
-                    help="also time the other workload shapes (guided step, 2048x2048, U-Net stages); off by default "
-                         "so that a kernel trace of the default command holds one shape per kernel")
+    ap.add_argument("--guidance-only", action="store_true",
+                    help="run only the fused guidance pass at its bandwidth-bound shape (batch 256 x 262144 elements) and "
+                         "print its roofline object: a kernel trace of this command holds that one launch shape")
+    ap.add_argument("--primary-only", action="store_true",
+                    help="time only the headline workload and the guidance pass (profiling runs: a kernel trace of "
+                         "this command then holds one shape per kernel); by default the other workload shapes "
+                         "(guided step, 2048x2048 and 2560x2560 branches, U-Net stages) are timed too")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the two guidance branches are batched or run "
@@ -192,6 +207,9 @@ def main():
     hb.lib()    # fails loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.guidance_only:
+        print(json.dumps({"guidance_pass_roofline": guidance_roofline(hb, torch, max(args.steps, 10), real_shapes=False)}))
+        return
     cfg = synth.CFG2
     t0 = time.time()
     m = model.MMDiT(cfg, synth.mmdit_globals(cfg), synth.mmdit_blocks(cfg))
@@ -239,12 +257,12 @@ def main():
     ach = d["work"] / d["launches"] / (dom_ms / d["launches"] * 1e-3) / 1e12
     roofline = {"kernel": dom if helper not in trace else dom + " + " + helper, "bound": "mfma", "achieved": ach,
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES.get(dom),
+                "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic_bytes().get(dom),
                 "us_per_launch": dom_ms / d["launches"] * 1e3, "flops_per_launch": d["work"] / d["launches"]}
 
     guidance = guidance_roofline(hb, torch, max(args.steps, 10))
     secondary = {}
-    if args.secondary:
+    if not args.primary_only:
         secondary = secondary_workloads(m, hb, model, synth, torch)
         del m
         torch.cuda.empty_cache()
@@ -253,10 +271,6 @@ def main():
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic", "mfma_frac_of_peak": tflops / PEAK_BF16_TFLOPS,
-        # the spec peak assumes 2.4 GHz; under this load the driver reports about 2.08 GHz (sampled during a
-        # 400-step run of this benchmark), which scales the peak accordingly
-        "mfma_frac_of_peak_at_sustained_clock": tflops / (PEAK_BF16_TFLOPS * SUSTAINED_SCLK_GHZ / SPEC_SCLK_GHZ),
-        "sustained_sclk_ghz": SUSTAINED_SCLK_GHZ,
         "config": {"workload": "configs[1]: SD3-shaped MMDiT branch, 1024x1024, 24 blocks, hidden 1536, "
                                "4096+333 tokens, batch 1, one denoiser forward", "algorithmic_tflop_per_step": flops / 1e12},
         "roofline": roofline, "guidance_pass_roofline": guidance, "kernels": kernels, "other_workloads": secondary, "setup_s": round(setup_s, 1),

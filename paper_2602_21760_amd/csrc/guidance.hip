@@ -180,17 +180,20 @@ int launch_guidance(const char* who, GuidanceArgs g, int batch, hyb_dtype vd, fl
     // algorithmic bytes: v_c + v_u read, x read, x_out written, plus the optional outputs
     const double vs = (double)hyb_dtype_size(vd);
     const double per_elem = 2 * vs + (g.x_out ? 8 : 0) + (g.x_lowp ? 2 : 0) + (g.v_out ? vs : 0);
-    HybTraceScope trace("guidance_pass", "byte", per_elem * (double)batch * (double)g.n, st);
-    if (vd == HYB_BF16) {
-        if (vec) hipLaunchKernelGGL((guidance_kernel<bf16_t, 8>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((guidance_kernel<bf16_t, 1>), grid, block, 0, st, g);
-    } else {
-        if (vec) hipLaunchKernelGGL((guidance_kernel<float, 8>), grid, block, 0, st, g);
-        else hipLaunchKernelGGL((guidance_kernel<float, 1>), grid, block, 0, st, g);
+    {   // the pass itself; the tiny finalisation below is a launch of its own
+        HybTraceScope trace("guidance_pass", "byte", per_elem * (double)batch * (double)g.n, st);
+        if (vd == HYB_BF16) {
+            if (vec) hipLaunchKernelGGL((guidance_kernel<bf16_t, 8>), grid, block, 0, st, g);
+            else hipLaunchKernelGGL((guidance_kernel<bf16_t, 1>), grid, block, 0, st, g);
+        } else {
+            if (vec) hipLaunchKernelGGL((guidance_kernel<float, 8>), grid, block, 0, st, g);
+            else hipLaunchKernelGGL((guidance_kernel<float, 1>), grid, block, 0, st, g);
+        }
     }
     int rc = hyb_check_launch(who);
     if (rc != HYB_OK) return rc;
     if (g.partial && (d1 || d2)) {
+        HybTraceScope trace("discrepancy_finalize", "byte", (double)batch * nblk * 32.0, st);
         hipLaunchKernelGGL(discrepancy_finalize_kernel, dim3(batch), dim3(HYB_WAVE), 0, st, g.partial, nblk, d1, d2);
         rc = hyb_check_launch(who);
     }
