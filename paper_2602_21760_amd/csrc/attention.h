@@ -16,7 +16,7 @@ struct AttnArgs {
                      // launch serve only the first n_q rows of a longer sequence (image-only queries over joint keys)
     float* part;     // scratch of hyb_attention_split_bytes() for the MFMA kernel's split tail, or nullptr (no splitting)
     // set by the launcher:
-    int tail_from, tail_units, tail_parts;
+    int tail_from, tail_units, tail_parts, tail_per_pair;
 };
 
 // Scratch the bf16 MFMA kernel wants for its split tail (see attention_mfma.hip); 0 when it would not split.

@@ -33,11 +33,13 @@
 //
 // Split tail.  All workgroups of a launch are usually resident at once (4 per CU), and a CU with 4 of
 // them takes a fifth longer than one with 3.  When an XCD holds a few more workgroups than a multiple
-// of its CU count (cfg 2: 105 on 32 CUs), those extra query blocks are therefore cut along the KEYS into
+// of its CU count (cfg 2: 105 on 32 CUs), that many query blocks are therefore cut along the KEYS into
 // 2 or 3 workgroups each, which leave unnormalised partial results (output accumulator, reference
 // maximum, normaliser) in a scratch buffer; a small second kernel merges them in a fixed order.  The
-// busiest CUs then carry 3 1/3 workgroups instead of 4.  Launches of several rounds cut their last
-// query blocks (two per CU) in halves the same way, against the ragged end of the launch.
+// busiest CUs then carry 3 1/3 workgroups instead of 4.  Launches of several rounds cut query blocks
+// (about two per CU) in halves the same way, against the ragged end of the launch.  The blocks that are
+// cut are the LAST u query blocks of EVERY (batch, head) pair, so a query row is treated the same way
+// whatever its sample or head: results stay independent of the batch index.
 #include "attention.h"
 
 #include <type_traits>
@@ -121,17 +123,23 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     int pair, qb;
     int part = 0, nparts = 1, unit = 0;   // split tail: this workgroup's share of the keys of query block `unit`
     if (pairs % 8 == 0) {
+        // XCD x serves pairs x, x + 8, ...: first the whole (uncut) query blocks of all its pairs, then the parts of the
+        // cut ones (the last tail_per_pair blocks of every pair)
         const int xcd = blockIdx.x % 8;
-        int j = blockIdx.x / 8;
+        const int j = blockIdx.x / 8;
+        const int whole = qblocks - a.tail_per_pair;   // uncut query blocks per pair
         if (a.tail_parts > 1 && j >= a.tail_from) {
             const int e = j - a.tail_from;
             nparts = a.tail_parts;
             part = e % nparts;
-            unit = xcd * a.tail_units + e / nparts;
-            j = a.tail_from + e / nparts;
+            const int t = e / nparts;                  // cut block of this XCD
+            unit = xcd * a.tail_units + t;
+            pair = xcd + 8 * (t / a.tail_per_pair);
+            qb = whole + t % a.tail_per_pair;
+        } else {
+            pair = xcd + 8 * (j / whole);
+            qb = j % whole;
         }
-        pair = xcd + 8 * (j / qblocks);
-        qb = j % qblocks;
     } else {
         pair = blockIdx.x / qblocks;
         qb = blockIdx.x % qblocks;
@@ -357,8 +365,8 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int lq = lane % 32, g = lane / 32;
     const int qblocks = (a.n_q + BQ - 1) / BQ;
-    const int unit = blockIdx.x, xcd = unit / a.tail_units, j = a.tail_from + unit % a.tail_units;
-    const int pair = xcd + 8 * (j / qblocks), qb = j % qblocks;
+    const int unit = blockIdx.x, xcd = unit / a.tail_units, t = unit % a.tail_units;
+    const int pair = xcd + 8 * (t / a.tail_per_pair), qb = qblocks - a.tail_per_pair + t % a.tail_per_pair;
     const int h = pair % a.heads, b = pair / a.heads;
     const int qrow = qb * BQ + wave * 32 + lq;
     if (qrow >= a.n_q) return;
@@ -402,10 +410,11 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
         }
 }
 
-// Split decision for a launch: per XCD there are w workgroups (XCD-pinned order) on cus CUs with 4 slots each.
-struct TailSplit { int from, units, parts; };
+// Split decision for a launch: per XCD there are w workgroups (XCD-pinned order) on cus CUs with 4 slots each.  The last
+// `per_pair` query blocks of every pair are cut into `parts`; `units` = cut blocks per XCD, `from` = whole blocks per XCD.
+struct TailSplit { int from, units, parts, per_pair; };
 TailSplit tail_split(int batch, int heads, int n_q) {
-    TailSplit t = {0, 0, 1};
+    TailSplit t = {0, 0, 1, 0};
     const int pairs = batch * heads;
     if (pairs == 0 || pairs % 8 != 0) return t;
     static int cus_per_xcd = 0;
@@ -414,19 +423,25 @@ TailSplit tail_split(int batch, int heads, int n_q) {
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = 256;
         cus_per_xcd = cus / 8;
     }
-    const int w = (pairs / 8) * ((n_q + BQ - 1) / BQ);
+    const int ppx = pairs / 8, qblocks = (n_q + BQ - 1) / BQ;
+    const int w = ppx * qblocks;
+    int per_pair, parts;
     if (w > 4 * cus_per_xcd) {
-        // more than one round: workgroups start as others finish, and the launch ends ragged; the last two
-        // workgroups' worth per CU are halved along the keys, which shortens that tail (cfg 3: -5 %, cfg 4: -3 %)
-        t.units = 2 * cus_per_xcd; t.from = w - t.units; t.parts = 2;
-        return t;
+        // more than one round: workgroups start as others finish, and the launch ends ragged; about two workgroups'
+        // worth per CU are halved along the keys, which shortens that tail (cfg 3: -5 %, cfg 4: -3 %)
+        per_pair = 2 * cus_per_xcd / ppx;
+        parts = 2;
+    } else {
+        const int extra = w % cus_per_xcd;
+        if (w < cus_per_xcd || extra == 0) return t;
+        per_pair = extra / ppx;                            // (a remainder of extra blocks stays whole)
+        if (per_pair == 0) return t;
+        parts = cus_per_xcd / (per_pair * ppx);            // the parts of all cut blocks fit one more workgroup per CU
+        if (parts > 3) parts = 3;
     }
-    const int full = w / cus_per_xcd * cus_per_xcd, extra = w - full;
-    if (full == 0 || extra == 0) return t;
-    int parts = cus_per_xcd / extra;                    // the parts of all extra blocks fit one more workgroup per CU
-    if (parts > 3) parts = 3;
-    if (parts < 2) return t;
-    t.from = full; t.units = extra; t.parts = parts;
+    if (per_pair > qblocks) per_pair = qblocks;
+    if (per_pair < 1 || parts < 2) return t;
+    t.per_pair = per_pair; t.units = per_pair * ppx; t.from = w - t.units; t.parts = parts;
     return t;
 }
 
@@ -439,13 +454,13 @@ size_t hyb_attention_split_bytes(int batch, int heads, int n_q) {
 
 int hyb_launch_attention_mfma(const AttnArgs& a0, hipStream_t st) {
     AttnArgs a = a0;
-    a.tail_from = a.tail_units = 0;
+    a.tail_from = a.tail_units = a.tail_per_pair = 0;
     a.tail_parts = 1;
     int blocks = ((a.n_q + BQ - 1) / BQ) * a.heads * a.batch;
     // the split needs the scratch, whole key tiles for every part, and text rows that are stored (o2) if there are any
-    const TailSplit t = a.part ? tail_split(a.batch, a.heads, a.n_q) : TailSplit{0, 0, 1};
+    const TailSplit t = a.part ? tail_split(a.batch, a.heads, a.n_q) : TailSplit{0, 0, 1, 0};
     if (t.parts > 1 && (a.n_kv + BKV - 1) / BKV >= 2 * t.parts) {
-        a.tail_from = t.from; a.tail_units = t.units; a.tail_parts = t.parts;
+        a.tail_from = t.from; a.tail_units = t.units; a.tail_parts = t.parts; a.tail_per_pair = t.per_pair;
         blocks = 8 * (t.from + t.units * t.parts);
     }
     dim3 grid(blocks), block(256);

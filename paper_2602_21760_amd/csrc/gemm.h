@@ -47,6 +47,9 @@ struct GemmGroup {
 int hyb_launch_gemm_simple(const GemmGroup& g, hyb_dtype in_dtype, hyb_dtype out_dtype, int epi, hipStream_t st);
 // bf16 MFMA kernel (k % 64 == 0, n % 8 == 0); returns -1 if the shape is not supported.
 int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st);
+// Large-tile bf16 MFMA kernel (256 x 128 tiles, one workgroup per CU).  Same accumulation order as the kernel above, hence
+// the same bits per token.  -1 when the shape or the epilogue has no large-tile form.
+int hyb_launch_gemm_mfma_big(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st);
 // Dispatch: MFMA for bf16 when supported, else the plain kernel.
 int hyb_launch_gemm(const GemmGroup& g, hyb_dtype in_dtype, hyb_dtype out_dtype, int epi, hipStream_t st);
 

@@ -467,6 +467,30 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
     return launch_tiles<OT, EPI, 2>(g, tiles_n, st);
 }
 
+// Long-k launches that fit ONE round of 256 x 128 tiles (one workgroup per CU) go to the large-tile kernel: there the
+// fixed cost of a tile (first-slab latency, epilogue: about 13 us with the gate + residual epilogue) is small against its
+// main loop, the operand stream per flop is a quarter smaller, and the launch neither ends in a half-filled round nor
+// pairs workgroups unevenly on the CUs (the SD3-shaped fc2, k = 6144: 216 tiles, 84 us alone and 96 us inside the step
+// against 101 and 103 us with 420 tiles of 128 x 128 on 512 slots).  With fewer k-slabs the 128 x 128 kernel is as fast
+// or faster (measured at k = 1536: 36.7 against 35.7 us inside the step).
+constexpr int kLargeTileMinSlabs = 48;
+bool use_large_tiles(const GemmGroup& g, hyb_dtype out_dtype, int epi) {
+    const bool f32 = out_dtype == HYB_F32;
+    const bool has_form = epi == EPI_BIAS || epi == EPI_GELU_TANH || epi == EPI_SILU || (epi == EPI_GATE_RES && f32);
+    if (!has_form || g.k / BK < kLargeTileMinSlabs) return false;
+    int tiles = 0;
+    for (int i = 0; i < g.count; i++) {
+        if (g.p[i].res2) return false;
+        tiles += ((g.p[i].m + 255) / 256) * ((g.n + 127) / 128);
+    }
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = 256;
+    }
+    return tiles <= cus && 2 * tiles > cus;
+}
+
 }  // namespace
 
 int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st) {
@@ -481,6 +505,10 @@ int hyb_launch_gemm_mfma(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipSt
         if (epi == EPI_QKV && (p.heads <= 0 || g.n % (p.heads * 64) != 0 || g.n / (p.heads * 64) > 3)) return -1;
     }
     const bool f32 = out_dtype == HYB_F32;
+    if (use_large_tiles(g, out_dtype, epi)) {
+        const int rc = hyb_launch_gemm_mfma_big(g, out_dtype, epi, st);
+        if (rc >= 0) return rc;
+    }
     switch (epi) {
         case EPI_BIAS: return f32 ? launch_epi<float, EPI_BIAS>(g, st) : launch_epi<bf16_t, EPI_BIAS>(g, st);
         case EPI_GELU_TANH: return f32 ? launch_epi<float, EPI_GELU_TANH>(g, st) : launch_epi<bf16_t, EPI_GELU_TANH>(g, st);

@@ -96,6 +96,20 @@ def test_block_batch_invariance_and_determinism(hb):
     assert np.array_equal(a_img, b_img) and np.array_equal(a_txt, b_txt)
 
 
+def test_block_with_large_tile_fc2_batch_invariance_and_parity(hb):
+    # hidden 768: the block's fc2 has k = 3072 and 2 x 3136 image + 2 x 77 text rows = 25 + 1 tile rows x 6 tile columns of
+    # 256 x 128 = 156 tiles, so it takes the large-tile kernel (image and text problem in one launch, the text tile
+    # straddling the two samples' gate rows); both samples carry the same data and must come out bit-identical, twice
+    cfg = synth.scaled(synth.CFG2, blocks=1, hidden=768, heads=12, latent_hw=112, n_txt=77, ctx_dim=128, batch=2)
+    assert cfg.n_img == 3136
+    a_img, a_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=40, same_rows=True)
+    assert np.array_equal(a_img[0], a_img[1]) and np.array_equal(a_txt[0], a_txt[1])
+    assert err(a_img, r_img) < TOL_BF16 and err(a_txt, r_txt) < TOL_BF16
+    assert err(a_img - x_img, r_img - x_img) < 5e-2
+    b_img, b_txt, _, _, _ = _block_case(hb, cfg, seed=40, same_rows=True, with_oracle=False)
+    assert np.array_equal(a_img, b_img) and np.array_equal(a_txt, b_txt)
+
+
 def test_block_without_text_and_empty_batch(hb):
     cfg = synth.scaled(synth.CFG2, blocks=1, hidden=128, heads=2, latent_hw=20, n_txt=0, ctx_dim=128, batch=1)
     g_img, g_txt, r_img, r_txt, _ = _block_case(hb, cfg, seed=30)

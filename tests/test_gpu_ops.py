@@ -240,3 +240,45 @@ def test_workload_gemms_take_the_mfma_path(hb):
         hb.hyb_trace_enable(False)
     assert names and all(nm.startswith(("gemm_mfma", "gemm_splitk")) for nm in names), sorted(names)
     assert sum(r["launches"] for nm, r in names.items() if nm.startswith("gemm_mfma")) == len(shapes) * 4
+
+
+def test_linear_large_tile_path(hb):
+    """Long-k launches that fit one round of 256 x 128 tiles take the large-tile kernel (the SD3-shaped fc2).  Every
+    epilogue it has, ragged rows (4429 = 17 x 256 + 77) and columns (1544 = 12 x 128 + 8), gate rows that change inside
+    a tile, against the oracle; the launch trace names the kernel; and, because both kernels accumulate in the same
+    order, the first rows computed alone by the 128 x 128 kernel have the same bits."""
+    m, n, k = 4429, 1544, 3072
+    a, w, b = _data(200, (m, k), "bf16"), _data(201, (n, k), "bf16", 0.02), _data(202, (n,), "f32", 0.02)
+    res, gate = _data(203, (m, n), "f32"), _data(204, (3, n), "f32")
+    da, dw, db = dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(b)
+    y = O.linear(a, w, b)
+    g_rows = gate[np.minimum(np.arange(m) // 1500, 2)]
+    cases = [("bias bf16", torch.bfloat16, hb.HYB_EPI_BIAS, {}, y, 4e-3),
+             ("bias f32", torch.float32, hb.HYB_EPI_BIAS, {}, y, 1e-4),
+             ("gelu", torch.bfloat16, hb.HYB_EPI_GELU_TANH, {}, O.gelu_tanh(y), 4e-3),
+             ("silu", torch.bfloat16, hb.HYB_EPI_SILU, {}, O.silu(y), 4e-3),
+             ("gate + residual", torch.float32, hb.HYB_EPI_GATE_RESIDUAL,
+              dict(residual=dev(res), gate=dev(gate), rows_per_gate=1500, gate_stride=n), res + g_rows * y, 1e-4)]
+    for name, odt, epi, kw, ref, bound in cases:
+        out = torch.empty(m, n, device="cuda", dtype=odt)
+        hb.hyb_trace_enable(True)
+        hb.hyb_linear(da, dw, db, out, epi, **kw)
+        torch.cuda.synchronize()
+        names = hb.hyb_trace_summary()
+        hb.hyb_trace_enable(False)
+        assert list(names) == ["gemm_mfma_256x128.epi%d.n%d.k%d" % (epi, n, k)], (name, names)
+        assert err(host(out), ref) < bound, name
+        # the first 100 rows alone: 12 tiles, far below one round -> the 128 x 128 kernel; same bits
+        small = torch.empty(100, n, device="cuda", dtype=odt)
+        kw_s = dict(kw, residual=dev(res[:100])) if kw else {}
+        hb.hyb_trace_enable(True)
+        hb.hyb_linear(da[:100], dw, db, small, epi, **kw_s)
+        torch.cuda.synchronize()
+        names = hb.hyb_trace_summary()
+        hb.hyb_trace_enable(False)
+        assert all(nm.startswith(("gemm_mfma_128x128", "gemm_mfma_64x128")) for nm in names), names
+        assert torch.equal(out[:100], small), name
+    # in place (out aliases the residual), as the block's fc2 runs
+    x = dev(res).clone()
+    hb.hyb_linear(da, dw, db, x, hb.HYB_EPI_GATE_RESIDUAL, residual=x, gate=dev(gate), rows_per_gate=1500, gate_stride=n)
+    assert err(host(x), res + g_rows * y) < 1e-4
