@@ -17,7 +17,8 @@ parts are marked "parity unpinned by the paper" (pinned instead by library speci
 cases, brute force and invariants in the CPU tests).
 
 Pins (tests/test_oracle_*.py): torch CPU fp64 library routines (layer_norm, group_norm,
-gelu, silu, scaled_dot_product_attention), pure-Python brute force on tiny inputs,
+gelu, silu, scaled_dot_product_attention; the modulated final layer re-assembled from layer_norm + linear),
+pure-Python brute force on tiny inputs,
 closed forms (CFG s=0/1, discrepancy of scaled branches, Euler telescoping, sigma
 closed form, constant velocity through the whole sampling loop) and structural invariants
 (zero modulation => identity block, key permutation invariance, softmax rows sum to one,
