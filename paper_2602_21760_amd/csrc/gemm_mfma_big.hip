@@ -138,14 +138,17 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
         if (r < BM) voff[c] = (min(row0 + r, m - 1) - row0) * (int)row_bytes + kv * 16;
         else voff[c] = (min(col0 + r - BM, n - 1) - col0) * (int)row_bytes + kv * 16;
     }
-    auto issue = [&](int slab, int stage) {
+    // chunks [c0, c1) of this wave's share of a slab
+    auto issue_chunks = [&](int slab, int stage, auto c0_tag, auto c1_tag) {
+        constexpr int C0 = decltype(c0_tag)::value, C1 = decltype(c1_tag)::value;
         const int soff = slab * (BK * 2);
 #pragma unroll
-        for (int c = 0; c < CPW; c++) {
+        for (int c = C0; c < C1; c++) {
             if (c < BM / 32) buffer_load_lds16(a_tile, a_tile_bytes, stage_base(stage) + (wave + 4 * c) * 1024, voff[c], soff);
             else buffer_load_lds16(w_tile, w_tile_bytes, stage_base(stage) + (wave + 4 * c) * 1024, voff[c], soff);
         }
     };
+    auto issue = [&](int slab, int stage) { issue_chunks(slab, stage, std::integral_constant<int, 0>{}, std::integral_constant<int, CPW>{}); };
 
     // Accumulators [feature tile][token tile].  They are never zeroed in registers: the first k-step of the first
     // slab multiplies into a constant-zero C operand (an accumulator file of 256 registers initialised through
@@ -236,7 +239,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
 
     auto mfma_step = [&](int set, auto first_tag, auto copies_tag) {
         constexpr bool FIRST = decltype(first_tag)::value;
-        constexpr bool WITH_COPIES = decltype(copies_tag)::value;
+        constexpr int COPIES = decltype(copies_tag)::value;      // slab copies issued next to this k-step
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int fn = 0; fn < TFW; fn++)
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
             for (int tm = 0; tm < TMW; tm++)
                 acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[set][fn], af[set][tm], FIRST ? zero : acc[fn][tm], 0, 0, 0);
         // the fragment reads of the next k-step (and, behind the barrier, the copies of the next free slab) between the MFMAs
-                if constexpr (WITH_COPIES) interleave_reads_and_copies<0, TMW * TFW, TMW + TFW, CPW>();
+        if constexpr (COPIES > 0) interleave_reads_and_copies<0, TMW * TFW, TMW + TFW, COPIES>();
         else interleave_reads<0, TMW + TFW, TMW * TFW>();
     };
     // Slab s sits in stage s % NST.  k-step kk uses fragment set kk % 2 and first requests the fragments of the next
@@ -252,7 +255,9 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     // share of slab s + 1 has landed (vmcnt: only the copies of younger slabs may be outstanding) and its reads of
     // slab s are complete (lgkmcnt), so behind the barrier slab s + 1 is readable and stage s % NST can be refilled
     // with slab s + NST.
-    auto slab_step = [&](int s, auto stage_tag, auto first_tag) {
+    constexpr int CQ = CPW / 4;                                // copies per k-step in the steady state
+    static_assert(CPW % 4 == 0, "a wave's copies of a slab are spread over the four k-steps");
+    auto slab_step = [&](int s, auto stage_tag, auto first_tag, bool first_quarter_only) {
         constexpr int STG = decltype(stage_tag)::value;
         constexpr bool FIRST_SLAB = decltype(first_tag)::value;
         if (s == nslab - 1) load_res(0, 0);
@@ -264,41 +269,57 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 __builtin_amdgcn_s_barrier();
-                if (s + NST < nslab) issue(s + NST, STG);
+                if (s + NST < nslab) {
+                    if (first_quarter_only) issue_chunks(s + NST, STG, std::integral_constant<int, 0>{}, std::integral_constant<int, CQ>{});
+                    else issue(s + NST, STG);
+                }
                 read_set((STG + 1) % NST, 0, 0);
             }
-            if (FIRST_SLAB && kk == 0) mfma_step(0, std::true_type{}, std::false_type{});
-            else mfma_step(kk & 1, std::false_type{}, std::false_type{});
+            if (FIRST_SLAB && kk == 0) mfma_step(0, std::true_type{}, std::integral_constant<int, 0>{});
+            else mfma_step(kk & 1, std::false_type{}, std::integral_constant<int, 0>{});
         }
     };
     // Steady state (slab s + NST exists): no conditions, so that the copies requested behind the barrier are spread
     // between the MFMAs of the same k-step instead of standing in front of them (a wave issues in order: sixteen
     // copy instructions in a row hold up the MFMAs behind them while the matrix pipe runs dry).
+    // The copies of a slab are spread over four k-steps (a quarter each), so that the copy path of the CU sees an even
+    // stream instead of a burst per slab: the first quarter of slab s + NST behind the barrier of slab s (which frees
+    // its buffer), the other three next to k-steps 0 .. 2 of slab s + 1.  On entry the first quarter of slab
+    // s + NST - 1 has been requested, its other quarters not.  The count of the wait is unchanged: the copies younger
+    // than those of slab s + 1 are the CPW copies of slab s + 2.
+    static_assert(NST == 3, "the steady state below is written for three slab buffers");
     auto slab_step_mid = [&](int s, auto stage_tag) {
         constexpr int STG = decltype(stage_tag)::value;
-#pragma unroll
-        for (int kk = 0; kk < 3; kk++) {
-            read_set(STG, kk + 1, (kk + 1) & 1);
-            mfma_step(kk & 1, std::false_type{}, std::false_type{});
-        }
+        read_set(STG, 1, 1);
+        issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, CQ>{}, std::integral_constant<int, 2 * CQ>{});
+        mfma_step(0, std::false_type{}, std::integral_constant<int, CQ>{});
+        read_set(STG, 2, 0);
+        issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, 2 * CQ>{}, std::integral_constant<int, 3 * CQ>{});
+        mfma_step(1, std::false_type{}, std::integral_constant<int, CQ>{});
+        read_set(STG, 3, 1);
+        issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, 3 * CQ>{}, std::integral_constant<int, CPW>{});
+        mfma_step(0, std::false_type{}, std::integral_constant<int, CQ>{});
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * CPW) : "memory");
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         read_set((STG + 1) % NST, 0, 0);
-        issue(s + NST, STG);
-        mfma_step(1, std::false_type{}, std::true_type{});
+        issue_chunks(s + NST, STG, std::integral_constant<int, 0>{}, std::integral_constant<int, CQ>{});
+        mfma_step(1, std::false_type{}, std::integral_constant<int, CQ>{});
     };
-    slab_step(0, std::integral_constant<int, 0>{}, std::true_type{});
+    const bool steady = 2 * NST < nslab;                    // the steady-state loop below runs at least once
+    slab_step(0, std::integral_constant<int, 0>{}, std::true_type{}, steady);
     int s = 1;
     for (; s + 2 * NST - 1 < nslab; s += NST) {
         slab_step_mid(s, std::integral_constant<int, 1 % NST>{});
         slab_step_mid(s + 1, std::integral_constant<int, 2 % NST>{});
         if constexpr (NST > 2) slab_step_mid(s + 2, std::integral_constant<int, 3 % NST>{});
     }
+    // the other quarters of the slab whose first quarter the last steady step requested (stage (s + NST - 1) % NST = 0)
+    if (steady) issue_chunks(s + NST - 1, 0, std::integral_constant<int, CQ>{}, std::integral_constant<int, CPW>{});
     for (; s < nslab; s += NST) {
-        slab_step(s, std::integral_constant<int, 1 % NST>{}, std::false_type{});
-        if (s + 1 < nslab) slab_step(s + 1, std::integral_constant<int, 2 % NST>{}, std::false_type{});
-        if (NST > 2 && s + 2 < nslab) slab_step(s + 2, std::integral_constant<int, 3 % NST>{}, std::false_type{});
+        slab_step(s, std::integral_constant<int, 1 % NST>{}, std::false_type{}, false);
+        if (s + 1 < nslab) slab_step(s + 1, std::integral_constant<int, 2 % NST>{}, std::false_type{}, false);
+        if (NST > 2 && s + 2 < nslab) slab_step(s + 2, std::integral_constant<int, 3 % NST>{}, std::false_type{}, false);
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();                          // every wave is done with the slab buffers
