@@ -467,12 +467,14 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
     return launch_tiles<OT, EPI, 2>(g, tiles_n, st);
 }
 
-// Long-k launches that fit ONE round of 256 x 128 tiles (one workgroup per CU) go to the large-tile kernel: there the
-// fixed cost of a tile (first-slab latency, epilogue: about 13 us with the gate + residual epilogue) is small against its
-// main loop, the operand stream per flop is a quarter smaller, and the launch neither ends in a half-filled round nor
-// pairs workgroups unevenly on the CUs (the SD3-shaped fc2, k = 6144: 216 tiles, 84 us alone and 96 us inside the step
-// against 101 and 103 us with 420 tiles of 128 x 128 on 512 slots).  With fewer k-slabs the 128 x 128 kernel is as fast
-// or faster (measured at k = 1536: 36.7 against 35.7 us inside the step).
+// Long-k launches with enough 256 x 128 tiles for more than half of the CUs go to the large-tile kernel (one
+// workgroup per CU): there the fixed cost of a tile (first-slab latency, epilogue: about 10 us with the gate + residual
+// epilogue) is small against its main loop, and the operand stream per flop is a quarter smaller (the SD3-shaped fc2,
+// k = 6144: 216 tiles in one round, 78 us alone and 90 us inside the step against 101 and 103 us with 420 tiles of
+// 128 x 128 on 512 slots; launches of several rounds, batch 2 or the 2048 x 2048 shape, gain 3-4 % per launch).  With
+// fewer k-slabs the 128 x 128 kernel, whose two workgroups per CU hide each other's fixed costs, is as fast or faster
+// (measured at k = 1536 inside the step: out-projection 35.0 against 35.4 us in one round, fc1 110 against 98 us in
+// four rounds).
 constexpr int kLargeTileMinSlabs = 48;
 bool use_large_tiles(const GemmGroup& g, hyb_dtype out_dtype, int epi) {
     const bool f32 = out_dtype == HYB_F32;
@@ -488,7 +490,7 @@ bool use_large_tiles(const GemmGroup& g, hyb_dtype out_dtype, int epi) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = 256;
     }
-    return tiles <= cus && 2 * tiles > cus;
+    return 2 * tiles > cus;
 }
 
 }  // namespace

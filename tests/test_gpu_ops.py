@@ -243,7 +243,7 @@ def test_workload_gemms_take_the_mfma_path(hb):
 
 
 def test_linear_large_tile_path(hb):
-    """Long-k launches that fit one round of 256 x 128 tiles take the large-tile kernel (the SD3-shaped fc2).  Every
+    """Long-k launches with enough 256 x 128 tiles take the large-tile kernel (the SD3-shaped fc2).  Every
     epilogue it has, ragged rows (4429 = 17 x 256 + 77) and columns (1544 = 12 x 128 + 8), gate rows that change inside
     a tile, against the oracle; the launch trace names the kernel; and, because both kernels accumulate in the same
     order, the first rows computed alone by the 128 x 128 kernel have the same bits."""
@@ -282,3 +282,15 @@ def test_linear_large_tile_path(hb):
     x = dev(res).clone()
     hb.hyb_linear(da, dw, db, x, hb.HYB_EPI_GATE_RESIDUAL, residual=x, gate=dev(gate), rows_per_gate=1500, gate_stride=n)
     assert err(host(x), res + g_rows * y) < 1e-4
+    # several rounds of large tiles (the rows twice: 70 x 13 tiles on 256 CUs): still the large-tile kernel, and each
+    # copy of a row gets the bits it got in the single round
+    da2 = torch.cat([da, da])
+    one, two = torch.empty(m, n, device="cuda", dtype=torch.bfloat16), torch.empty(2 * m, n, device="cuda", dtype=torch.bfloat16)
+    hb.hyb_linear(da, dw, db, one, hb.HYB_EPI_GELU_TANH)
+    hb.hyb_trace_enable(True)
+    hb.hyb_linear(da2, dw, db, two, hb.HYB_EPI_GELU_TANH)
+    torch.cuda.synchronize()
+    names = hb.hyb_trace_summary()
+    hb.hyb_trace_enable(False)
+    assert list(names) == ["gemm_mfma_256x128.epi%d.n%d.k%d" % (hb.HYB_EPI_GELU_TANH, n, k)], names
+    assert torch.equal(two[:m], one) and torch.equal(two[m:], one)
