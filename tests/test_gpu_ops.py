@@ -242,6 +242,26 @@ def test_workload_gemms_take_the_mfma_path(hb):
     assert sum(r["launches"] for nm, r in names.items() if nm.startswith("gemm_mfma")) == len(shapes) * 4
 
 
+@pytest.mark.parametrize("k", [3136, 3200, 3264])
+def test_linear_large_tile_slab_count_remainders(hb, k):
+    """The large-tile kernel's pipeline ends in three, four or five slabs outside its steady-state loop
+    (49, 50, 51 k-slabs here): against the oracle, and the same bits as the 128 x 128 kernel on the first rows."""
+    m, n = 2816, 1536
+    a, w, b = _data(210 + k, (m, k), "bf16"), _data(211 + k, (n, k), "bf16", 0.02), _data(212, (n,), "f32", 0.02)
+    da, dw, db = dev(a, torch.bfloat16), dev(w, torch.bfloat16), dev(b)
+    out = torch.empty(m, n, device="cuda", dtype=torch.float32)
+    hb.hyb_trace_enable(True)
+    hb.hyb_linear(da, dw, db, out)
+    torch.cuda.synchronize()
+    names = hb.hyb_trace_summary()
+    hb.hyb_trace_enable(False)
+    assert list(names) == ["gemm_mfma_256x128.epi%d.n%d.k%d" % (hb.HYB_EPI_BIAS, n, k)], names
+    assert err(host(out), O.linear(a, w, b)) < 1e-4
+    small = torch.empty(100, n, device="cuda", dtype=torch.float32)
+    hb.hyb_linear(da[:100], dw, db, small)
+    assert torch.equal(out[:100], small)
+
+
 def test_linear_large_tile_path(hb):
     """Long-k launches with enough 256 x 128 tiles take the large-tile kernel (the SD3-shaped fc2).  Every
     epilogue it has, ragged rows (4429 = 17 x 256 + 77) and columns (1544 = 12 x 128 + 8), gate rows that change inside
