@@ -475,14 +475,14 @@ int launch_epi(const GemmGroup& g, hipStream_t st) {
 // fewer k-slabs the 128 x 128 kernel, whose two workgroups per CU hide each other's fixed costs, is as fast or faster
 // (measured at k = 1536 inside the step: out-projection 35.0 against 35.4 us in one round, fc1 110 against 98 us in
 // four rounds).
-constexpr int kLargeTileMinSlabs = 48;
+constexpr int kLargeTileMinSlabs = 48;          // launches of several rounds
+constexpr int kLargeTileMinSlabsOneRound = 32;  // launches of one round (the SDXL-shaped down-projection, k = 2560)
 bool use_large_tiles(const GemmGroup& g, hyb_dtype out_dtype, int epi) {
     const bool f32 = out_dtype == HYB_F32;
     const bool has_form = epi == EPI_BIAS || epi == EPI_GELU_TANH || epi == EPI_SILU || (epi == EPI_GATE_RES && f32);
-    if (!has_form || g.k / BK < kLargeTileMinSlabs) return false;
+    if (!has_form || g.k / BK < kLargeTileMinSlabsOneRound) return false;
     int tiles = 0;
     for (int i = 0; i < g.count; i++) {
-        if (g.p[i].res2) return false;
         tiles += ((g.p[i].m + 255) / 256) * ((g.n + 127) / 128);
     }
     static int cus = 0;
@@ -490,7 +490,7 @@ bool use_large_tiles(const GemmGroup& g, hyb_dtype out_dtype, int epi) {
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) cus = 256;
     }
-    return 2 * tiles > cus;
+    return 2 * tiles > cus && (tiles <= cus || g.k / BK >= kLargeTileMinSlabs);
 }
 
 }  // namespace

@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     GemmProblem p;
 #define HYB_SEL(f) p.f = second ? g.p[1].f : g.p[0].f
     HYB_SEL(a); HYB_SEL(w); HYB_SEL(bias); HYB_SEL(out); HYB_SEL(m);
-    HYB_SEL(res); HYB_SEL(gate); HYB_SEL(rows_per_gate); HYB_SEL(gate_stride);
+    HYB_SEL(res); HYB_SEL(res2); HYB_SEL(gate); HYB_SEL(rows_per_gate); HYB_SEL(gate_stride);
 #undef HYB_SEL
     const int m = p.m, n = g.n, k = g.k, m_end = p.m;
     int row0, col0;
@@ -224,6 +224,8 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     // (two residual buffers; a 256 x 256 geometry with its 256 accumulators would have room for one)
     constexpr int RES_BUFS = TFW >= 4 ? 1 : 2;
     f32x4 resv[RES ? RES_BUFS : 1][RES ? ITERS : 1];
+    f32x4 res2v[RES ? RES_BUFS : 1][RES ? ITERS : 1];         // the optional second residual (same pieces)
+    const bool two_res = RES && p.res2 != nullptr;
     const int wrow0 = row0 + wt * 32 * TMW, wcol0 = col0 + wf * WCOLS;   // the wave's corner of the tile
     auto load_res = [&](int tm, int buf) {
         if constexpr (RES) {
@@ -234,6 +236,10 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
             };
 #pragma unroll
             for (int j = 0; j < ITERS; j++) resv[buf][j] = *reinterpret_cast<const f32x4*>(p.res + piece_offset(j));
+            if (two_res) {
+#pragma unroll
+                for (int j = 0; j < ITERS; j++) res2v[buf][j] = *reinterpret_cast<const f32x4*>(p.res2 + piece_offset(j));
+            }
         }
     };
 
@@ -386,7 +392,8 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
             const int f = wcol0 + pc * CHUNK_ELEMS;
             const unsigned char* srcp = stg + prow * STRIDE + pc * 16;
             if constexpr (RES) {
-                const f32x4 y = *reinterpret_cast<const f32x4*>(srcp) + resv[tm % RES_BUFS][j];
+                f32x4 y = *reinterpret_cast<const f32x4*>(srcp) + resv[tm % RES_BUFS][j];
+                if (two_res) y += res2v[tm % RES_BUFS][j];
                 if (r < m_end && f < n) *reinterpret_cast<f32x4*>(static_cast<float*>(p.out) + (size_t)r * n + f) = y;
             } else {
                 const u32x4 y = *reinterpret_cast<const u32x4*>(srcp);
@@ -427,14 +434,12 @@ int launch_big(const GemmGroup& g, hipStream_t st) {
 }  // namespace
 
 // Large-tile launch (256 x 128 tiles) of a group of up to two problems.  Epilogues: bias, GELU-tanh, SiLU (either output
-// type), gate * y + residual (fp32 output, single residual).  Returns -1 when the shape or the epilogue has no large-tile
+// type), gate * y + residual(s) (fp32 output).  Returns -1 when the shape or the epilogue has no large-tile
 // form.  The caller has validated the group as for hyb_launch_gemm_mfma.
 int hyb_launch_gemm_mfma_big(const GemmGroup& g, hyb_dtype out_dtype, int epi, hipStream_t st) {
     if (g.k <= 0 || g.k % BK != 0 || g.n % 8 != 0 || g.n < 8) return -1;
     if ((size_t)g.k * 2 * 256 >= ((size_t)1 << 31)) return -1;    // per-lane byte offsets inside a tile's operand rows are 32-bit
     if (g.k / BK < 3) return -1;                                  // the prologue requests the first three slabs
-    for (int i = 0; i < g.count; i++)
-        if (g.p[i].res2) return -1;
     const bool f32 = out_dtype == HYB_F32;
     switch (epi) {
         case EPI_BIAS: return f32 ? launch_big<float, EPI_BIAS, 4, 2>(g, st) : launch_big<bf16_t, EPI_BIAS, 4, 2>(g, st);
