@@ -1,7 +1,7 @@
 // Large-tile bf16 MFMA GEMM for gfx950: the same contraction as gemm_mfma.hip (out = epilogue(A W^T + bias),
 // A [m, k] tokens x features-in, W [n, k] features-out x features-in, fp32 accumulation in
 // v_mfma_f32_32x32x16_bf16, k in slabs of 64, identical order of accumulation, so a token's result has the
-// same bits whichever of the two kernels computes it), for long-k launches that fit ONE round of 256 x 128 tiles.
+// same bits whichever of the two kernels computes it), for long-k launches with enough 256 x 128 tiles for the chip.
 //
 // Why a second geometry.  With 128 x 128 tiles, two workgroups per CU, a launch of 420 tiles and 96 k-slabs (the
 // SD3-shaped fc2: n = 1536, k = 6144) is one round in which 164 CUs carry two tiles and 92 carry one, every tile pays
@@ -10,12 +10,13 @@
 // same launch): a wave owns 128 x 64 outputs = 4 x 2 MFMA tiles (128 accumulator registers); per k-slab the CU copies
 // 48 KB for the same MFMA work, and a wave reads 0.75 KB of fragments per MFMA instead of 1 KB.  One wave per SIMD is
 // enough for the MFMA pipe as long as nothing stands in front of its MFMAs in program order (a wave issues in order):
-// fragment reads AND slab copies are spread between the MFMAs.
+// fragment reads AND slab copies are spread between the MFMAs, the copies of a slab over a whole slab period (a
+// quarter per k-step), so that the CU's copy path, which takes about 16 clocks per 1 KB request, never queues up.
 //
 // Main loop: as in gemm_mfma.hip (direct-to-LDS 16-byte buffer loads with the slab offset as the scalar
 // operand, XOR-swizzled unpadded 128-byte rows, explicit vmcnt / lgkmcnt waits and ONE raw barrier per slab), with
-// THREE slab buffers (a copy is in flight for two slab periods: a lone workgroup has no neighbour on its CU to fill
-// a stall) and the fragments of a k-step in two register sets: the reads of k-step j + 1 are issued between the
+// THREE slab buffers (a copy is in flight for one to two slab periods: a lone workgroup has no neighbour on its CU to
+// fill a stall) and the fragments of a k-step in two register sets: the reads of k-step j + 1 are issued between the
 // MFMAs of k-step j, across the slab boundary.  The slab buffers are separate arrays, so that the compiler knows
 // that a copy into one and a fragment read from another do not alias and interleaves them freely.
 //
