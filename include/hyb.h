@@ -149,6 +149,18 @@ int hyb_joint_attention_ws(const void* q, const void* k, const void* v, void* o,
                            hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
 size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dtype dtype);
 
+/* The same attention (workspace form) for queries that already carry the softmax scale and the change of base:
+ * q holds q * scale * log2(e), so that q k^T is the exponent of 2 and o = softmax_2(q k^T) v, which is
+ * softmax(q_unscaled k^T * scale) v.  A producer that rounds q to bf16 anyway (hyb_block_forward's QKV
+ * projection does this) folds the factor in before its one rounding and loses nothing.  The bf16 kernel
+ * then first tries the sums without a reference maximum (P = 2^score, one instruction per score less, no row
+ * maxima); a workgroup whose row sums leave [2^-64, 2^64] (scores of more than about +-50 in base 2) starts
+ * over with the running-maximum form, so the result is defined for every finite input.  Same shapes,
+ * workspace and error behaviour as hyb_joint_attention_ws. */
+int hyb_joint_attention_prescaled(const void* q, const void* k, const void* v, void* o,
+                                  int batch, int heads, int n_q, int n_kv, int head_dim,
+                                  hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
+
 /* out[b, r] = sum_k w[r, k] * SiLU(temb[b, k]) + bias[r]: the adaLN modulation vectors of any
  * number of blocks / streams at once (stack their weight matrices along rows).
  * w: device [rows, hidden] of `dtype`; bias: device float[rows]; temb: device float[batch, hidden];

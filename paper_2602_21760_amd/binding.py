@@ -74,6 +74,7 @@ SIGNATURES = {
     "hyb_joint_attention": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp]),
     "hyb_joint_attention_ws": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _sz, _vp]),
     "hyb_joint_attention_workspace_bytes": (_sz, [_i, _i, _i, _i]),
+    "hyb_joint_attention_prescaled": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _sz, _vp]),
     "hyb_adaln_modulation": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp]),
     "hyb_layernorm_modulate": (_i, [_vp, _vp, _vp, _sz, _vp, _i, _i, _i, _f, _i, _vp]),
     "hyb_linear": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp, _vp, _i, _sz, _vp]),
@@ -226,6 +227,14 @@ def hyb_joint_attention_ws(q, k, v, o, workspace, scale=0.0):
     B, H, Nq, d = q.shape
     _check(lib().hyb_joint_attention_ws(_p(q), _p(k, q.dtype), _p(v, q.dtype), _p(o, q.dtype), B, H, Nq, k.shape[2], d,
                                         scale, _dt(q), _p(workspace), _nbytes(workspace), _stream()))
+    return o
+
+
+def hyb_joint_attention_prescaled(q, k, v, o, workspace):
+    """hyb_joint_attention_ws for q that already holds q * scale * log2(e)."""
+    B, H, Nq, d = q.shape
+    _check(lib().hyb_joint_attention_prescaled(_p(q), _p(k, q.dtype), _p(v, q.dtype), _p(o, q.dtype), B, H, Nq, k.shape[2], d,
+                                               _dt(q), _p(workspace), _nbytes(workspace), _stream()))
     return o
 
 

@@ -14,6 +14,8 @@ struct AttnArgs {
     float scale;     // > 0
     int q_stride;    // query rows stored per (batch, head) in q (>= n_q); 0 means n_q.  A larger stride lets a
                      // launch serve only the first n_q rows of a longer sequence (image-only queries over joint keys)
+    int prescaled;   // q already carries scale x log2(e) (the QKV epilogue of the joint block stores it so): the kernel
+                     // then exponentiates the raw scores in base 2 and `scale` is not used
     float* part;     // scratch of hyb_attention_split_bytes() for the MFMA kernel's split tail, or nullptr (no splitting)
     // set by the launcher:
     int tail_from, tail_units, tail_parts, tail_per_pair;

@@ -31,6 +31,19 @@
 // Tail keys are masked to -inf before the row maximum; tail query rows are clamped on load
 // and not stored.  The reduction order is fixed: results are deterministic and batch-invariant.
 //
+// Prescaled queries (template parameter PRE; the joint block's QKV projection stores q times scale x log2(e)
+// before its one rounding to bf16).  The kernel is bound by its vector instructions, and with the factor
+// already in q the scores are exponents of 2 as they leave the MFMA.  A workgroup then first takes all its
+// key tiles with reference 0: P = 2^score, no row maxima, no exchange with lane ^ 32, no test for a grown
+// maximum and no FMA per score (57 of 131 vector instructions per tile and wave less).  The sums of such a
+// pass are exact as long as they stay far from the ends of the fp32 range: after the last tile every row's
+// sum must lie in [2^-64, 2^64] (terms of up to 2^64 leave the accumulators below 2^64 x 64 x |v|; a sum
+// of at least 2^-64 means the terms that matter are normal numbers in bf16 as well).  If any row of the
+// workgroup fails (the four waves agree through a flag in LDS, so that all of them keep reaching the same
+// barriers) the workgroup starts over with the running-maximum loop described above; which path a
+// workgroup takes depends on its own 128 query rows and its keys only.  A part of a split unit records its
+// reference (0 or the running maximum) like any other, and the merge treats both alike.
+//
 // Split tail.  All workgroups of a launch are usually resident at once (4 per CU), and a CU with 4 of
 // them takes a fifth longer than one with 3.  When an XCD holds a few more workgroups than a multiple
 // of its CU count (cfg 2: 105 on 32 CUs), that many query blocks are therefore cut along the KEYS into
@@ -109,6 +122,7 @@ __device__ __forceinline__ void lds_wait(bf16x4 (&vh)[2][2][2], bf16x8 (&vf)[2][
         }
 }
 
+template <bool PRE>
 __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     // [buffer][K tile | V tile]
     __shared__ __attribute__((aligned(16))) unsigned char smem[2][2 * TILE_BYTES];
@@ -191,7 +205,8 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         }
     };
 
-    const float c = a.scale * 1.4426950408889634f;   // scores are exponentiated in base 2
+    // scores are exponentiated in base 2; PRE: q came pre-multiplied by scale x log2(e), the scores are base-2 exponents
+    const float c = PRE ? 1.f : a.scale * 1.4426950408889634f;
     float m_run = -__builtin_inff(), l_run = 0.f;
     f32x16 o[2];
 #pragma unroll
@@ -224,8 +239,9 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 
     const int nt = (a.n_kv + BKV - 1) / BKV;
     const int t_begin = part * nt / nparts, t_end = (part + 1) * nt / nparts;   // this workgroup's key tiles
-    auto tile = [&](int t, auto buf_tag) {
+    auto tile = [&](int t, auto buf_tag, auto direct_tag) {
         constexpr int BUF = decltype(buf_tag)::value;
+        constexpr bool DIRECT = decltype(direct_tag)::value;   // P = 2^s without a reference maximum (see below)
         constexpr int BUF_OFF = BUF * 2 * TILE_BYTES;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of tile t has landed
         __builtin_amdgcn_s_barrier();                      // ... everyone's; and the other buffer is free again
@@ -270,34 +286,41 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
                     if (key >= a.n_kv) s[kt][i] = -__builtin_inff();
                 }
         }
-        // v_max3_f32 directly: fmaxf() makes the compiler canonicalise every MFMA output first (one extra
-        // multiply per score), which costs more than the maxima themselves
-        float mx = s[0][0], my = s[1][0];      // two chains: half the dependent latency
-#pragma unroll
-        for (int i = 1; i < 15; i += 2) {
-            mx = max3(mx, s[0][i], s[0][i + 1]);
-            my = max3(my, s[1][i], s[1][i + 1]);
-        }
-        mx = max3(mx, s[0][15], s[1][15]);
-        mx = max_with_other_half(max3(mx, my, my));
-        // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
-        const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
-        if (__any(grow)) {
-            const float m_new = grow ? mx : m_run;
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);   // 1 where unchanged, 0 on the first tile
-            m_run = m_new;
-            l_run *= corr;
-#pragma unroll
-            for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-                for (int i = 0; i < 16; i++) o[dt][i] *= corr;
-        }
-        const float mc = m_run * c;
         bf16x8 pb[2][2];
+        if constexpr (DIRECT) {
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++)
+            for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
+                for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(s[kt][i]);
+        } else {
+            // v_max3_f32 directly: fmaxf() makes the compiler canonicalise every MFMA output first (one extra
+            // multiply per score), which costs more than the maxima themselves
+            float mx = s[0][0], my = s[1][0];      // two chains: half the dependent latency
+#pragma unroll
+            for (int i = 1; i < 15; i += 2) {
+                mx = max3(mx, s[0][i], s[0][i + 1]);
+                my = max3(my, s[1][i], s[1][i + 1]);
+            }
+            mx = max3(mx, s[0][15], s[1][15]);
+            mx = max_with_other_half(max3(mx, my, my));
+            // advance the running maximum only when it would grow by more than 2^RESCALE_LOG2
+            const bool grow = (mx - m_run) * c > RESCALE_LOG2;      // first tile: m_run = -inf -> true
+            if (__any(grow)) {
+                const float m_new = grow ? mx : m_run;
+                const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * c);   // 1 where unchanged, 0 on the first tile
+                m_run = m_new;
+                l_run *= corr;
+#pragma unroll
+                for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+                    for (int i = 0; i < 16; i++) o[dt][i] *= corr;
+            }
+            const float mc = m_run * c;
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)__builtin_amdgcn_exp2f(fmaf(s[kt][i], c, -mc));
+        }
 
         // O^T += V^T P^T (the fragments of the other 32 features take the registers the scores leave)
         v_frags<BUF, 1>(vbase[1], vh[1]);
@@ -322,11 +345,44 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
             for (int hf = 0; hf < 2; hf++) o[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[1][kt][hf], pb[kt][hf], o[1], 0, 0, 0);
     };
-    issue(t_begin, 0);
-    for (int t = t_begin; t < t_end; t += 2) {
-        tile(t, std::integral_constant<int, 0>{});
-        if (t + 1 < t_end) tile(t + 1, std::integral_constant<int, 1>{});
+#define HYB_KEY_LOOP(direct_tag)                                                  \
+    issue(t_begin, 0);                                                            \
+    for (int t = t_begin; t < t_end; t += 2) {                                    \
+        tile(t, std::integral_constant<int, 0>{}, direct_tag);                    \
+        if (t + 1 < t_end) tile(t + 1, std::integral_constant<int, 1>{}, direct_tag); \
     }
+    if constexpr (PRE) {
+        // With scores that are base-2 exponents already, the first attempt keeps no reference maximum at all: P = 2^s,
+        // reference 0.  Softmax does not depend on the reference, and scaling by a power of two is exact, so this is the
+        // same result as long as nothing leaves the range of fp32 / bf16; it saves the row maxima, the rescaling test and
+        // the subtraction per score (57 of 131 vector instructions per key tile and wave).  The attempt is valid when every
+        // row's sum of probabilities ends up well inside the range (then no probability that matters was flushed and
+        // nothing overflowed); otherwise the whole workgroup (uniform decision through LDS, so that every wave passes
+        // the same barriers) starts over with the running-maximum form.
+        m_run = 0.f;
+        HYB_KEY_LOOP(std::true_type{})
+        const float l_row = l_run + __shfl_xor(l_run, 32, 64);
+        const bool out_of_range = !(l_row > 0x1p-64f && l_row < 0x1p+64f);    // also true for NaN
+        const int wave_bad = __any(out_of_range) ? 1 : 0;
+        __syncthreads();                                     // every wave is done with the tile buffers
+        volatile int* flags = reinterpret_cast<volatile int*>(&smem[0][0]);
+        if (lane == 0) flags[wave] = wave_bad;
+        __syncthreads();                                     // (waits for the LDS write before the barrier)
+        const bool again = (flags[0] | flags[1] | flags[2] | flags[3]) != 0;
+        __syncthreads();                                     // the flags are read before the buffers are refilled
+        if (again) {
+            m_run = -__builtin_inff();
+            l_run = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) o[dt][i] = 0.f;
+            HYB_KEY_LOOP(std::false_type{})
+        }
+    } else {
+        HYB_KEY_LOOP(std::false_type{})
+    }
+#undef HYB_KEY_LOOP
 
     if (qrow >= a.n_q) return;
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -370,7 +426,7 @@ __global__ __launch_bounds__(256) void attention_merge_kernel(AttnArgs a) {
     const int h = pair % a.heads, b = pair / a.heads;
     const int qrow = qb * BQ + wave * 32 + lq;
     if (qrow >= a.n_q) return;
-    const float c = a.scale * 1.4426950408889634f;
+    const float c = a.prescaled ? 1.f : a.scale * 1.4426950408889634f;
     const float* src = a.part + (size_t)unit * PARTS * PART_FLOATS + tid;
     // everything this thread needs, requested at once
     float val[PARTS][34];
@@ -466,7 +522,8 @@ int hyb_launch_attention_mfma(const AttnArgs& a0, hipStream_t st) {
     dim3 grid(blocks), block(256);
     {
         HybTraceScope trace("attention_mfma", "flop", 4.0 * a.batch * a.heads * (double)a.n_q * a.n_kv * 64, st);
-        hipLaunchKernelGGL(attention_mfma_kernel, grid, block, 0, st, a);
+        if (a.prescaled) hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, block, 0, st, a);
+        else hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, block, 0, st, a);
     }
     int rc = hyb_check_launch("attention_mfma");
     if (rc != HYB_OK || a.tail_parts == 1) return rc;

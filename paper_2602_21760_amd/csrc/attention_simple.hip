@@ -69,7 +69,7 @@ int hyb_launch_attention(const AttnArgs& a, hyb_dtype dtype, hipStream_t st) {
 namespace {
 int joint_attention(const char* who, const void* q, const void* k, const void* v, void* o,
                     int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
-                    hyb_dtype dtype, void* workspace, size_t workspace_bytes, bool with_ws, void* stream) {
+                    hyb_dtype dtype, void* workspace, size_t workspace_bytes, bool with_ws, bool prescaled, void* stream) {
     HYB_CHECK_DTYPE(dtype);
     HYB_REQUIRE(batch >= 0 && heads >= 0 && n_q >= 0 && n_kv >= 0, HYB_ERR_SHAPE, "%s: negative size", who);
     HYB_REQUIRE(head_dim == 64, HYB_ERR_SHAPE, "%s: head_dim %d is not supported (only 64)", who, head_dim);
@@ -79,6 +79,12 @@ int joint_attention(const char* who, const void* q, const void* k, const void* v
     HYB_CHECK_PTR(q); HYB_CHECK_PTR(k); HYB_CHECK_PTR(v); HYB_CHECK_PTR(o);
     HYB_CHECK_ALIGN(q); HYB_CHECK_ALIGN(k); HYB_CHECK_ALIGN(v); HYB_CHECK_ALIGN(o);
     AttnArgs a = {q, k, v, o, nullptr, n_q, batch, heads, n_q, n_kv, scale > 0.f ? scale : 0.125f};
+    if (prescaled) {
+        // q carries scale x log2(e): the bf16 kernel exponentiates the raw scores in base 2; the fp32 kernel, which
+        // exponentiates scale x score in base e, gets scale = ln 2
+        a.prescaled = dtype == HYB_BF16;
+        a.scale = 0.6931471805599453f;
+    }
     if (with_ws) {
         const size_t need = hyb_joint_attention_workspace_bytes(batch, heads, n_q, dtype);
         if (need > 0) {
@@ -94,7 +100,7 @@ int joint_attention(const char* who, const void* q, const void* k, const void* v
 extern "C" int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
                                    int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
                                    hyb_dtype dtype, void* stream) {
-    return joint_attention("hyb_joint_attention", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, nullptr, 0, false, stream);
+    return joint_attention("hyb_joint_attention", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, nullptr, 0, false, false, stream);
 }
 
 extern "C" size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dtype dtype) {
@@ -105,5 +111,11 @@ extern "C" size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int 
 extern "C" int hyb_joint_attention_ws(const void* q, const void* k, const void* v, void* o,
                                       int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
                                       hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
-    return joint_attention("hyb_joint_attention_ws", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, workspace, workspace_bytes, true, stream);
+    return joint_attention("hyb_joint_attention_ws", q, k, v, o, batch, heads, n_q, n_kv, head_dim, scale, dtype, workspace, workspace_bytes, true, false, stream);
+}
+
+extern "C" int hyb_joint_attention_prescaled(const void* q, const void* k, const void* v, void* o,
+                                             int batch, int heads, int n_q, int n_kv, int head_dim,
+                                             hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream) {
+    return joint_attention("hyb_joint_attention_prescaled", q, k, v, o, batch, heads, n_q, n_kv, head_dim, 0.f, dtype, workspace, workspace_bytes, true, true, stream);
 }

@@ -141,6 +141,8 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
             p.a = h[s]; p.w = sw[s]->w_qkv; p.bias = sw[s]->b_qkv;
             p.q = ws + L.q; p.k = ws + L.k; p.v = ws + L.v;
             p.tokens = ntok[s] > 0 ? ntok[s] : 1; p.tok_offset = toff[s]; p.n_total = N; p.heads = d.heads;
+            // the bf16 attention kernel takes queries that already carry 1/sqrt(64) x log2(e) (one rounding either way)
+            if (dt == HYB_BF16) p.q_scale = 0.125f * 1.4426950408889634f;
         }
         if ((rc = hyb_launch_gemm(g, dt, dt, EPI_QKV, st))) return rc;
     }
@@ -151,6 +153,7 @@ extern "C" int hyb_block_forward(const hyb_block_desc* desc, const hyb_block_wei
         if (!has_img) { a.o = o[1]; a.o2 = nullptr; a.split = N; }
         if (!has_txt) { a.o2 = nullptr; a.split = N; }
         if (txt_pre_only) { a.n_q = Ni; a.o2 = nullptr; a.split = Ni; }   // image queries only, joint keys
+        a.prescaled = dt == HYB_BF16;
         if ((rc = hyb_launch_attention(a, dt, st))) return rc;
     }
     // 4. x = x + gate1 * (o Wout^T + b)

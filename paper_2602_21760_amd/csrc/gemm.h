@@ -32,6 +32,8 @@ struct GemmProblem {
     // element -> {q,k,v}[((b * heads + head) * n_total) + tok_offset + t][i]
     void* q; void* k; void* v;
     int tokens, tok_offset, n_total, heads;
+    float q_scale;       // EPI_QKV: the q part is multiplied by this before it is rounded (0 means 1): lets the attention
+                         // kernel take queries that already carry softmax scale x log2(e)
 };
 
 struct GemmGroup {
@@ -61,6 +63,7 @@ __device__ __forceinline__ void gemm_store_scalar(const GemmProblem& p, int epi,
         const int hd = p.heads * 64;
         const int which = c / hd, cc = c % hd, head = cc / 64, i = cc % 64;
         const int b = r / p.tokens, t = r % p.tokens;
+        if (which == 0 && p.q_scale != 0.f) v *= p.q_scale;
         OT* base = static_cast<OT*>(which == 0 ? p.q : (which == 1 ? p.k : p.v));
         base[(((size_t)b * p.heads + head) * p.n_total + p.tok_offset + t) * 64 + i] = from_f32<OT>(v);
         return;

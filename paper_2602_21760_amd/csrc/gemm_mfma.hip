@@ -204,6 +204,8 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     read_set(0, 0);
     read_set(0, 1);
     constexpr bool GEGLU = EPI == EPI_GEGLU;
+    [[maybe_unused]] const int q_cols = EPI == EPI_QKV && p.q_scale != 0.f ? p.heads * 64 : 0;   // columns of the q part that are scaled
+    [[maybe_unused]] const float q_scale = p.q_scale;
     constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
     constexpr int NPASS = (F32OUT && TMW == 2) ? 2 : 1;   // a 128-token fp32 tile is staged in two 64-token halves
     constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
@@ -312,6 +314,8 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
                             for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
                         } else if constexpr (EPI == EPI_GATE_RES) {
                             v *= gv[fn][gi];
+                        } else if constexpr (EPI == EPI_QKV) {
+                            if (col0 + fl < q_cols) v *= q_scale;      // the four features of v lie in one head
                         }
                         unsigned char* dst = smem + trow * STRIDE + fl * SE;
                         if constexpr (F32OUT) {

@@ -18,12 +18,14 @@ def hb():
     return binding
 
 
-def _block_case(hb, cfg, seed=0, same_rows=False, with_oracle=True):
+def _block_case(hb, cfg, seed=0, same_rows=False, with_oracle=True, tweak=None):
     """Run one joint block on the GPU and in the oracle on the same inputs."""
     from paper_2602_21760_amd import binding as B
     rng_dt = cfg.dtype
     D = cfg.hidden
     w = synth.mmdit_block_weights(cfg, 0)
+    if tweak:
+        tweak(w)
     x_img = synth.normal(seed + 1, (cfg.batch, cfg.n_img, D), 1.0, "f32")
     x_txt = synth.normal(seed + 2, (cfg.batch, cfg.n_txt, D), 1.0, "f32")
     temb = synth.normal(seed + 3, (cfg.batch, D), 1.0, "f32")
@@ -85,6 +87,30 @@ def test_block_attention_with_split_tail(hb):
     assert err(g_img[:, 4096:] - x_img[:, 4096:], r_img[:, 4096:] - x_img[:, 4096:]) < 5e-2
     # the merge adds the parts in a fixed order: a second run gives the same bits
     g_img2, g_txt2, _, _, _ = _block_case(hb, cfg, seed=31, with_oracle=False)
+    assert np.array_equal(g_img, g_img2) and np.array_equal(g_txt, g_txt2)
+
+
+def test_block_attention_scores_far_from_zero(hb):
+    """The block's bf16 attention first sums 2^score without a reference maximum and starts a workgroup over with
+    the running maximum when a row sum leaves the range it accepts.  Head 0 gets all its scores shifted by about
+    +92 (in base-2 units), head 1 by -92, through a constant key component (zero weight row, bias 16) times a
+    query bias of +-32: a shift leaves the softmax as it is, so the oracle's result keeps its smooth weights while
+    the kernel overflows / underflows in its first attempt; heads 2 and 3 stay in range."""
+    cfg = synth.scaled(synth.CFG2, blocks=1, hidden=256, heads=4, latent_hw=36, n_txt=77, ctx_dim=128, batch=2, dtype="bf16")
+    D = cfg.hidden
+
+    def tweak(w):
+        for s in ("img", "txt"):
+            for head, shift in ((0, 32.0), (1, -32.0)):
+                w[s]["qkv_b"][head * 64] = shift
+                w[s]["qkv_w"][D + head * 64] = 0.0
+                w[s]["qkv_b"][D + head * 64] = 16.0
+
+    g_img, g_txt, r_img, r_txt, (x_img, _) = _block_case(hb, cfg, seed=50, tweak=tweak)
+    assert np.isfinite(g_img).all() and np.isfinite(g_txt).all()
+    assert err(g_img, r_img) < TOL_BF16 and err(g_txt, r_txt) < TOL_BF16
+    assert err(g_img - x_img, r_img - x_img) < 5e-2
+    g_img2, g_txt2, _, _, _ = _block_case(hb, cfg, seed=50, with_oracle=False, tweak=tweak)
     assert np.array_equal(g_img, g_img2) and np.array_equal(g_txt, g_txt2)
 
 

@@ -219,6 +219,78 @@ def test_attention_with_workspace_splits_and_matches(hb, shape):
             hb.hyb_joint_attention_ws(dq, dk, dv, o_ws, ws[:need - 256])
 
 
+LN2 = 0.6931471805599453
+
+
+def _prescaled(hb, q, k, v, dt="bf16", fill=None):
+    B, H, Nq, _ = q.shape
+    need = hb.hyb_joint_attention_workspace_bytes(B, H, Nq, hb.HYB_BF16 if dt == "bf16" else hb.HYB_F32)
+    ws = torch.empty(max(need, 256), device="cuda", dtype=torch.uint8)
+    if fill is not None:
+        ws.fill_(fill)
+    o = torch.empty(B, Nq, H * 64, device="cuda", dtype=tdt(dt))
+    hb.hyb_joint_attention_prescaled(dev(q, tdt(dt)), dev(k, tdt(dt)), dev(v, tdt(dt)), o, ws)
+    return o
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ATTN_SHAPES)
+def test_attention_prescaled(hb, dt, shape):
+    """Queries that already hold scale x log2(e): the result is the base-2 softmax of q k^T, i.e. the oracle's
+    attention with scale = ln 2.  Scores of a few units: the bf16 kernel's sums without a reference maximum."""
+    B, H, Nq, Nk = shape
+    q, k, v = _data(240, (B, H, Nq, 64), dt, 0.2), _data(241, (B, H, Nk, 64), dt), _data(242, (B, H, Nk, 64), dt)
+    got = host(_prescaled(hb, q, k, v, dt))
+    assert err(got, O.attention(q, k, v, scale=LN2)) < (tol(dt) if dt == "f32" else 1e-2)
+
+
+@pytest.mark.parametrize("case", ["overflow", "underflow", "some_rows", "edge_of_range"])
+def test_attention_prescaled_out_of_range_sums_start_over(hb, case):
+    """Row sums of 2^score outside [2^-64, 2^64] make a workgroup start over with the running maximum: scores of
+    hundreds (every row), scores near -130 (every term underflows), a few huge rows inside otherwise moderate
+    128-row blocks, and sums a little inside / outside the accepted range on both sides."""
+    B, H, N = 1, 2, 461
+    q, k, v = _data(250, (B, H, N, 64), "bf16", 0.2), _data(251, (B, H, N, 64), "bf16"), _data(252, (B, H, N, 64), "bf16")
+    if case == "overflow":
+        q, k = q * 32, k * 4
+    elif case == "underflow":
+        q[..., 0], k[..., 0] = -16.0, 8.0 + 0.25 * np.round(k[..., 0])
+    elif case == "some_rows":
+        q[0, 0, 130:140] *= 64
+        q[0, 1, 300] *= 256
+        q[0, 1, 460, 0], k[0, 1, :, 0] = -32.0, 4.0
+    else:
+        # head 0: row r gets the constant (r - 230) / 2.8 added to all its scores: sums from about 2^-73 to 2^91
+        k[0, 0, :, 0] = 8.0
+        q[0, 0, :, 0] = synth.round_bf16(((np.arange(N) - 230) / 2.8 / 8).astype(np.float32))
+    o1 = _prescaled(hb, q, k, v)
+    got = host(o1)
+    assert np.isfinite(got).all()
+    assert err(got, O.attention(q, k, v, scale=LN2)) < 1e-2
+    assert torch.equal(o1, _prescaled(hb, q, k, v))
+
+
+def test_attention_prescaled_split_parts_with_mixed_references(hb):
+    """The shape whose last query blocks are cut along the keys: the first thousand keys of half the heads give
+    scores of hundreds, so the key parts that hold them start over (reference = row maximum) while the other parts
+    of the same rows keep reference 0, and the merge has to bring both onto one scale; the other heads stay
+    moderate throughout.  Sampled rows against the oracle, all rows against the form with the scale passed in,
+    twice for identical bits with the scratch overwritten in between."""
+    B, H, N = 1, 8, 5118
+    q, k, v = _data(260, (B, H, N, 64), "bf16", 0.2), _data(261, (B, H, N, 64), "bf16"), _data(262, (B, H, N, 64), "bf16")
+    k[0, :4, :1000] *= 32
+    o1 = _prescaled(hb, q, k, v)
+    o2 = _prescaled(hb, q, k, v, fill=0xFF)
+    assert torch.equal(o1, o2)
+    rows = np.unique(np.concatenate([np.arange(N - 300, N), [0, 1, 127, 128], np.random.default_rng(5).integers(0, N, 40)]))
+    assert err(host(o1)[:, rows], O.attention(q, k, v, rows=rows, scale=LN2)) < 1e-2
+    need = hb.hyb_joint_attention_workspace_bytes(B, H, N, hb.HYB_BF16)
+    ws = torch.empty(need, device="cuda", dtype=torch.uint8)
+    o3 = torch.empty_like(o1)
+    hb.hyb_joint_attention_ws(*(dev(a, torch.bfloat16) for a in (q, k, v)), o3, ws, scale=LN2)
+    assert err(host(o1), host(o3)) < 1e-2
+
+
 def test_workload_gemms_take_the_mfma_path(hb):
     """Every bf16 GEMM shape of the SD3-shaped and SDXL-shaped workloads (k % 64 == 0, n % 8 == 0) is served by
     the MFMA kernel: the library's launch trace names the kernel each call ran, and none is the plain FMA one."""
