@@ -99,8 +99,10 @@ extern "C" int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb
         gg.splitk_ws = ws + L.splitk; gg.splitk_bytes = L.splitk_bytes;
         return gg;
     };
+    constexpr float kQScale = 0.125f * 1.4426950408889634f;      // softmax scale 1 / sqrt(64) times log2(e)
     auto attn = [&](void* q, void* k, void* v, int n_kv) {
         AttnArgs a = {q, k, v, o, nullptr, T, B, d.heads, T, n_kv, 0.125f};
+        a.prescaled = dt == HYB_BF16;      // the q projections below store q times scale x log2(e) in that case
         return hyb_launch_attention(a, dt, st);
     };
 
@@ -113,6 +115,7 @@ extern "C" int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb
         GemmProblem& p = gg.p[0];
         p.a = h; p.w = w->w_qkv1; p.q = ws + L.q; p.k = ws + L.k; p.v = ws + L.v;
         p.tokens = T; p.tok_offset = 0; p.n_total = T; p.heads = d.heads;
+        if (dt == HYB_BF16) p.q_scale = kQScale;
         if ((rc = hyb_launch_gemm(gg, dt, dt, EPI_QKV, st))) return rc;
     }
     if ((rc = attn(ws + L.q, ws + L.k, ws + L.v, T))) return rc;
@@ -129,6 +132,7 @@ extern "C" int hyb_sdxl_block_forward(const hyb_sdxl_block_desc* desc, const hyb
         GemmProblem& p = gg.p[0];
         p.a = h; p.w = w->w_q2; p.q = ws + L.q;
         p.tokens = T; p.tok_offset = 0; p.n_total = T; p.heads = d.heads;
+        if (dt == HYB_BF16) p.q_scale = kQScale;
         if ((rc = hyb_launch_gemm(gg, dt, dt, EPI_QKV, st))) return rc;
     }
     {
