@@ -51,6 +51,23 @@ def test_attention_against_library_sdpa():
     np.testing.assert_array_equal(O.attention(q, k, v, scale=0.0), O.attention(q, k, v))
 
 
+def test_attention_with_prescaled_queries_is_the_same_softmax():
+    """What the GPU tests of hyb_joint_attention_prescaled compare against: with q' = q * scale * log2(e) the
+    weights 2^(q' k) / sum 2^(q' k) are the softmax of q k * scale, i.e. the oracle's attention at scale = ln 2
+    on q'; checked here against the library routine on the unscaled q and by brute force in base 2."""
+    B, H, Nq, Nk, d = 1, 2, 9, 21, 64
+    q, k, v = _rand(14, B, H, Nq, d), _rand(15, B, H, Nk, d), _rand(16, B, H, Nk, d)
+    qp = q * (0.125 * math.log2(math.e))
+    got = O.attention(qp, k, v, scale=math.log(2.0))
+    ref = F.scaled_dot_product_attention(*(torch.from_numpy(a) for a in (q, k, v)))
+    np.testing.assert_allclose(got, ref.permute(0, 2, 1, 3).reshape(B, Nq, H * d).numpy(), rtol=1e-11, atol=1e-13)
+    for h in range(H):
+        for i in range(Nq):
+            w = [2.0 ** float(np.dot(qp[0, h, i], k[0, h, j])) for j in range(Nk)]
+            row = sum(w[j] * v[0, h, j] for j in range(Nk)) / sum(w)
+            np.testing.assert_allclose(got[0, i, h * d:(h + 1) * d], row, rtol=1e-11, atol=1e-13)
+
+
 def test_attention_invariants():
     B, H, Nq, Nk, d = 1, 2, 6, 10, 8
     q, k, v = _rand(7, B, H, Nq, d), _rand(8, B, H, Nk, d), _rand(9, B, H, Nk, d)
