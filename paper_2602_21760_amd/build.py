@@ -1,4 +1,5 @@
-"""Build libhyb.so from csrc/*.hip with hipcc for gfx950 (in-tree, next to this file)."""
+"""Build libhyb.so from csrc/*.hip with hipcc for gfx950 (in-tree, next to this file), and the stand-alone measurement
+aids under probes/ (one executable per source, next to it)."""
 import concurrent.futures as cf
 import glob
 import os
@@ -9,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhyb.so")
+PROBES = os.path.join(HERE, "probes")
 
 # packed fp32 ops are disabled on purpose (hipcc flag, see the build notes of this target)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -32,6 +34,15 @@ def _compile(src):
     return obj, r.stderr
 
 
+def _probe(src):
+    exe = src[:-4]
+    cmd = [_hipcc()] + [f for f in HIPCC_FLAGS if f != "-fPIC"] + [src, "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+    return exe, r.stderr
+
+
 def build(verbose=False, jobs=8):
     os.makedirs(OBJ, exist_ok=True)
     srcs = sorted(glob.glob(os.path.join(CSRC, "*.hip")))
@@ -39,6 +50,11 @@ def build(verbose=False, jobs=8):
         raise RuntimeError("no sources under " + CSRC)
     objs = []
     with cf.ThreadPoolExecutor(max_workers=jobs) as ex:
+        probes = [ex.submit(_probe, src) for src in sorted(glob.glob(os.path.join(PROBES, "*.hip")))]
+        for fut in probes:
+            _, err = fut.result()
+            if verbose and err.strip():
+                sys.stderr.write(err)
         for obj, err in ex.map(_compile, srcs):
             objs.append(obj)
             if verbose and err.strip():
