@@ -8,6 +8,8 @@
 // addresses and swizzles, the phases held in program order, workgroups of 4 waves with a barrier per tile, the tile
 // copies global -> LDS.  Operands are either constants or roughly normal random bf16 values: the clock that the chip's
 // power management grants under MFMA load depends on how many bits toggle.
+// Two more rows give the yardstick: a loop of nothing but independent MFMAs on register operands, for the 32x32x16 and the
+// 16x16x32 form (the same flop count per row: 16 and 32 MFMAs per step).
 // Prints a table of SIMD time per wave and tile and the MFMA rate of the whole chip.
 #include <hip/hip_runtime.h>
 
@@ -20,6 +22,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef void __attribute__((address_space(3)))* lptr_t;
 
 #define CK(x)                                                                             \
@@ -163,6 +166,66 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
     out[((size_t)blockIdx.x * 1024 + threadIdx.x) % (256 * 1024)] = r;
 }
 
+// Nothing but MFMAs: 4 (32x32x16) or 8 (16x16x32) independent accumulators, operands in registers.
+template <int WIDE>
+__global__ __launch_bounds__(1024) void bare_kernel(float* out, int n, int random_regs) {
+    bf16x8 a[4], b[4];
+    for (int j = 0; j < 4; j++)
+        for (int i = 0; i < 8; i++) {
+            unsigned h = (threadIdx.x * 2654435761u) ^ ((unsigned)(i * 40503u + j * 9973u) * 2246822519u);
+            h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+            a[j][i] = random_regs ? (bf16_t)(((int)(h & 0xffff) - 32768) * (1.7f / 32768.0f)) : (bf16_t)0.0625f;
+            b[j][i] = random_regs ? (bf16_t)(((int)(h >> 16) - 32768) * (1.7f / 32768.0f)) : (bf16_t)0.125f;
+        }
+    float r = 0.f;
+    if (WIDE) {
+        f32x16 acc[4];
+        for (int c = 0; c < 4; c++)
+            for (int i = 0; i < 16; i++) acc[c][i] = 0.f;
+        for (int it = 0; it < n; it++) {
+#pragma unroll
+            for (int j = 0; j < 16; j++) acc[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j & 3], b[(j >> 2) & 3], acc[j & 3], 0, 0, 0);
+            if ((it & 63) == 63)
+                for (int c = 0; c < 4; c++)
+                    for (int i = 0; i < 16; i++) acc[c][i] *= 0.001f;
+        }
+        for (int c = 0; c < 4; c++)
+            for (int i = 0; i < 16; i++) r += acc[c][i];
+    } else {
+        f32x4 acc[8];
+        for (int c = 0; c < 8; c++)
+            for (int i = 0; i < 4; i++) acc[c][i] = 0.f;
+        for (int it = 0; it < n; it++) {
+#pragma unroll
+            for (int j = 0; j < 32; j++) acc[j & 7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j & 3], b[(j >> 3) & 3], acc[j & 7], 0, 0, 0);
+            if ((it & 63) == 63)
+                for (int c = 0; c < 8; c++)
+                    for (int i = 0; i < 4; i++) acc[c][i] *= 0.001f;
+        }
+        for (int c = 0; c < 8; c++)
+            for (int i = 0; i < 4; i++) r += acc[c][i];
+    }
+    out[((size_t)blockIdx.x * 1024 + threadIdx.x) % (256 * 1024)] = r;
+}
+
+template <int WIDE>
+float run_bare(float* out, int n, int random_regs, int waves_per_simd, int cus) {
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    float ms = 0.f;
+    for (int rep = 0; rep < 3; rep++) {
+        CK(hipEventRecord(e0));
+        bare_kernel<WIDE><<<cus, 256 * waves_per_simd>>>(out, n, random_regs);
+        CK(hipEventRecord(e1));
+        CK(hipEventSynchronize(e1));
+        CK(hipEventElapsedTime(&ms, e0, e1));
+    }
+    CK(hipEventDestroy(e0));
+    CK(hipEventDestroy(e1));
+    return ms;
+}
+
 template <int FLAGS>
 float run(float* out, int n, const unsigned char* kv, int random_regs, int waves_per_simd, int cus) {
     hipEvent_t e0, e1;
@@ -215,8 +278,10 @@ int main() {
                    16.0 * 32768.0 * simds * n * w / (ms * 1e-3) * 1e-12);
         };
         for (int w = 2; w <= 4; w += 2) {
-            row("MFMAs and conversions only, operands in registers", w, run<F_NO_EXP>(out, n, kv, random, w, cus));
-            row("MFMAs and conversions only, fragments from LDS", w, run<F_NO_EXP | F_LDS>(out, n, kv, random, w, cus));
+            row("independent MFMAs 32x32x16 only", w, run_bare<1>(out, n, random, w, cus));
+            row("independent MFMAs 16x16x32 only (32 per step)", w, run_bare<0>(out, n, random, w, cus));
+            row("the tile's MFMAs and conversions, operands in registers", w, run<F_NO_EXP>(out, n, kv, random, w, cus));
+            row("the tile's MFMAs and conversions, fragments from LDS", w, run<F_NO_EXP | F_LDS>(out, n, kv, random, w, cus));
             row("whole tile, operands in registers", w, run<0>(out, n, kv, random, w, cus));
             row("whole tile, fragments from LDS", w, run<F_LDS>(out, n, kv, random, w, cus));
             row("... phases in program order", w, run<F_LDS | F_ORDER>(out, n, kv, random, w, cus));
