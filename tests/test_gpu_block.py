@@ -178,6 +178,39 @@ def test_cfg1_end_to_end_fp32(hb):
     assert d1.item() == 0.0 and d2.item() == 0.0
 
 
+def test_forward_replays_from_a_captured_graph_bit_identically(hb):
+    """The library neither allocates nor synchronises, so a branch forward can be captured into a HIP graph (callers
+    that replay the step without launch overhead do this).  A reduced SD3-shaped model whose attention takes the split
+    tail (its merge kernel and scratch are inside the graph): the replay is compared with the eager result three times,
+    with eager forwards and synchronisations in between."""
+    from paper_2602_21760_amd import model
+    cfg = synth.scaled(synth.CFG2, blocks=2, hidden=256, heads=4, latent_hw=142, n_txt=77, ctx_dim=128, batch=2)
+    assert cfg.n_img + cfg.n_txt == 5118
+    m = model.MMDiT(cfg, synth.mmdit_globals(cfg), synth.mmdit_blocks(cfg))
+    lat, ctx_c, ctx_u = synth.mmdit_inputs(cfg)
+    latent = dev(np.stack([lat, lat]))
+    ctx = dev(np.stack([ctx_c, ctx_u]))
+    t = torch.full((2,), 0.5, device="cuda")
+    ref = m.forward(latent, ctx, t).clone()
+    side = torch.cuda.Stream()                       # capture happens on a stream of its own, at the default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        m.forward(latent, ctx, t)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        out = m.forward(latent, ctx, t)
+    torch.cuda.synchronize()
+    for _ in range(3):
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+        assert torch.equal(m.forward(latent, ctx, t), ref)
+        torch.cuda.synchronize()
+
+
 def test_reduced_bf16_forward_and_guided_loop(hb):
     """The guided sampling loop (both branches batched, fused guidance pass every step) on a reduced
     SD3-shaped model: 4 blocks, hidden 256, 324 + 77 tokens, 6 steps of the shifted schedule."""
