@@ -78,9 +78,12 @@ __device__ __forceinline__ float wave_max(float v) {
 // correctly rounded quotient costs about ten extra instructions per element in the GEMM epilogues.
 __device__ __forceinline__ float silu_f(float z) { return z * __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 __device__ __forceinline__ float gelu_tanh_f(float z) {
-    // 0.5 z (1 + tanh(u)) = z * sigmoid(2u), u = sqrt(2/pi) (z + 0.044715 z^3)
-    const float u = 0.7978845608028654f * (z + 0.044715f * z * z * z);
-    return z * __builtin_amdgcn_rcpf(1.0f + __expf(-2.0f * u));
+    // 0.5 z (1 + tanh(u)) = z * sigmoid(2u) = z / (1 + 2^(-2 u log2(e))), u = sqrt(2/pi) (z + 0.044715 z^3); the constants
+    // are folded into the cubic, so that an element costs seven instructions: -2 u log2(e) = z (k1 + k3 z^2)
+    constexpr float k1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;
+    constexpr float k3 = k1 * 0.044715f;
+    const float arg = z * fmaf(z * z, k3, k1);
+    return z * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(arg));
 }
 // Exact-erf GELU with erf from the rational approximation 7.1.26 of Abramowitz & Stegun,
 // erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p x), x >= 0 (absolute error < 1.5e-7, far inside
