@@ -155,8 +155,9 @@ size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dt
  * projection does this) folds the factor in before its one rounding and loses nothing.  The bf16 kernel
  * then first tries the sums without a reference maximum (P = 2^score, one instruction per score less, no row
  * maxima); a workgroup whose row sums leave [2^-64, 2^64] (scores of more than about +-50 in base 2) starts
- * over with the running-maximum form, so the result is defined for every finite input.  Same shapes,
- * workspace and error behaviour as hyb_joint_attention_ws. */
+ * over with the running-maximum form, so the result is defined for every finite input.  HYB_F32 inputs take the
+ * plain fp32 kernel with scale = ln 2.  Same shapes, workspace and error behaviour as hyb_joint_attention_ws
+ * (Sec. 3 of the paper: the attention inside one evaluation of the denoiser). */
 int hyb_joint_attention_prescaled(const void* q, const void* k, const void* v, void* o,
                                   int batch, int heads, int n_q, int n_kv, int head_dim,
                                   hyb_dtype dtype, void* workspace, size_t workspace_bytes, void* stream);
