@@ -1,23 +1,27 @@
 // bf16 MFMA GEMM for gfx950: out = epilogue(A W^T + bias), A [m, k] tokens x features-in,
-// W [n, k] features-out x features-in, fp32 accumulation in v_mfma_f32_32x32x16_bf16.
+// W [n, k] features-out x features-in, fp32 accumulation in v_mfma_f32_16x16x32_bf16.
 //
-// Tiling: a workgroup of 4 waves (2 x 2) owns a 128 x 128 output tile; each wave owns 2 x 2 MFMA
-// tiles of 32 x 32 (small problems: 64 x 128 tiles, 1 x 2 MFMA tiles per wave, see launch_epi).
-// The weight fragment is the MFMA "A" operand and the token fragment the "B" operand, so the 16
-// accumulator registers of a lane run along the output-feature axis (4 consecutive features per
-// group of 4 registers, one token per lane).
+// Tiling: a workgroup of 4 waves (2 x 2) owns a 128 x 128 output tile; each wave owns 4 x 4 MFMA
+// tiles of 16 x 16 (small problems: 64 x 128 tiles, 4 x 2 MFMA tiles per wave, see launch_epi).
+// The weight fragment is the MFMA "A" operand and the token fragment the "B" operand, so the 4
+// accumulator registers of a tile run along the output-feature axis (4 consecutive features, one
+// token per lane).  The 16 x 16 x 32 form is used because it is the cheaper one on this chip: it
+// moves half the accumulator bytes per multiply-add of the 32 x 32 x 16 form, and under the power
+// limit that sets the clock of these kernels the main loop runs 5-6 % faster with it (QKV-shaped and
+// fc1 launches of the SD3-shaped workload); the sums come out bit for bit the same as with the
+// 32 x 32 x 16 form that the large-tile kernel uses (the tests compare the two kernels' outputs).
 //
 // Main loop: k is cut into slabs of 64.  A slab of both operands (128 + 128 rows of 128 bytes) is
 // copied global -> LDS by 16-byte direct-to-LDS buffer loads (buffer_load_dwordx4 ... lds: a wave fills 1 KB
 // of LDS per instruction, no VGPR staging, no ds_write; the slab's byte offset is the scalar operand and the
 // per-lane offsets are loop invariants, so a slab costs no vector address arithmetic), double buffered: the copy
 // of slab s + 1 runs while slab s is multiplied.  LDS rows are unpadded; the 16-byte slots of a row are XOR-swizzled
-// with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 16 consecutive rows hit distinct
+// with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 8 consecutive rows hit distinct
 // banks (the swizzle is applied on the global side: each lane picks which 16 bytes it fetches).
 // Waits on the copies are explicit (s_waitcnt vmcnt + s_barrier); a full __syncthreads() would
-// force vmcnt(0) on every barrier through its fence.  The fragments of the four k-steps of a slab
-// live in a ring of four register sets and are read two k-steps ahead of the MFMAs that use them,
-// also across the slab boundary, which leaves a single barrier per slab (before k-step 2).
+// force vmcnt(0) on every barrier through its fence.  The fragments of the two k-steps (of 32) of a
+// slab live in two register sets and are read one k-step ahead of the MFMAs that use them, also
+// across the slab boundary, which leaves a single barrier per slab (before its second k-step).
 //
 // Epilogue: the accumulators (+ bias, activation, gate) are staged through LDS (reusing the slab
 // buffers) and written out row-contiguously, 16 bytes per lane, so that global stores and the
@@ -102,7 +106,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // uniform: LDS copy targets (M0) become scalar arithmetic
     const int wt = wave % 2, wf = wave / 2;          // wave position: tokens, features
-    const int lr = lane % 32, hi = lane / 32;
+    const int l16 = lane % 16, q4 = lane / 16;      // MFMA 16x16x32: row / column of the lane, its quarter of the 32 k
 
     // This wave's chunks of a slab: chunk c covers stage rows 8 c .. 8 c + 7 (rows 0..BM-1 = A, then 128 rows of W);
     // lane i fills 16-byte slot i % 8 of row i / 8 and fetches k-vector (slot ^ swz(row)) for it.
@@ -138,43 +142,45 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
         }
     };
 
-    f32x16 acc[2][TMW];   // [feature tile][token tile]
+    constexpr int TT = 2 * TMW;   // token tiles of 16 per wave
+    f32x4 acc[4][TT];             // [feature tile of 16][token tile of 16]
 #pragma unroll
-    for (int fn = 0; fn < 2; fn++)
+    for (int fi = 0; fi < 4; fi++)
 #pragma unroll
-        for (int tm = 0; tm < TMW; tm++)
+        for (int ti = 0; ti < TT; ti++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) acc[fn][tm][i] = 0.f;
+            for (int i = 0; i < 4; i++) acc[fi][ti][i] = 0.f;
 
-    // Fragment addresses inside a stage.  With the XOR swizzle the 16-byte slot of the read for k-step kk of
-    // MFMA tile t is (lane part) ^ 2 (kk ^ 2 t), so four per-lane bases per operand cover all the reads of
-    // a slab and the tile row block (t * 32 rows) is an immediate offset.  (With 32 token rows per wave the
-    // wave's own row offset 32 wt also reaches bit 2 of the swizzle; it is folded into the lane part.)
-    const int lb = (hi ^ lr ^ (lr >> 3)) & 7;
+    // Fragment addresses inside a stage.  A fragment of v_mfma_f32_16x16x32_bf16 is 16 rows x 32 k: lane (l16, q4) reads
+    // the 16 bytes of row l16 that hold k = 32 ks + 8 q4 .. + 7, i.e. 16-byte slot 4 ks + q4 of the row.  With the XOR
+    // swizzle and tile rows 16 t + l16 that slot sits at (lane part) ^ (4 ks ^ 2 t): four per-lane bases per operand
+    // cover all the reads of a slab, and the tile row block (t * 16 rows) is an immediate offset.  (With 32 token rows per
+    // wave the wave's own row offset 32 wt also reaches bit 2 of the swizzle; it is folded into the lane part.)
+    const int lb = (q4 ^ (l16 & 7) ^ (l16 >> 3)) & 7;
     const int lb_a = TMW == 1 ? lb ^ (4 * wt) : lb;
     int a_base[4], w_base[4];
 #pragma unroll
     for (int c = 0; c < 4; c++) {
-        a_base[c] = (wt * 32 * TMW + lr) * ROWB + ((lb_a ^ (2 * c)) * 16);
-        w_base[c] = BM * ROWB + (wf * 64 + lr) * ROWB + ((lb ^ (2 * c)) * 16);
+        a_base[c] = (wt * 32 * TMW + l16) * ROWB + ((lb_a ^ (2 * c)) * 16);
+        w_base[c] = BM * ROWB + (wf * 64 + l16) * ROWB + ((lb ^ (2 * c)) * 16);
     }
-    // Ring of four fragment sets, one per k-step of a slab; the reads run two k-steps ahead of their use,
-    // across the slab boundary.
-    bf16x8 af[4][TMW], wfr[4][2];
-    auto read_set = [&](int stage, int kk) {
+    // Two fragment sets, one per k-step of 32 of a slab; the reads run one k-step ahead of their use, across the slab
+    // boundary.
+    bf16x8 af[2][TT], wfr[2][4];
+    auto read_set = [&](int stage, int ks) {
         const unsigned char* base = smem + stage * STAGE_BYTES;
 #pragma unroll
-        for (int t = 0; t < TMW; t++)
-            af[kk][t] = *reinterpret_cast<const bf16x8*>(base + a_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+        for (int t = 0; t < TT; t++)
+            af[ks][t] = *reinterpret_cast<const bf16x8*>(base + a_base[((2 * ks) ^ t) & 3] + t * 16 * ROWB);
 #pragma unroll
-        for (int t = 0; t < 2; t++)
-            wfr[kk][t] = *reinterpret_cast<const bf16x8*>(base + w_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+        for (int t = 0; t < 4; t++)
+            wfr[ks][t] = *reinterpret_cast<const bf16x8*>(base + w_base[((2 * ks) ^ t) & 3] + t * 16 * ROWB);
     };
 
-    // Main loop.  Slab s sits in stage s % 2.  ONE barrier per slab, before k-step 2: by then every wave has
+    // Main loop.  Slab s sits in stage s % 2.  ONE barrier per slab, before its second k-step: by then every wave has
     // issued (and, after the lgkmcnt wait, completed) all its reads of slab s, so stage s % 2 can be refilled with
     // slab s + 2 right behind the barrier, and the copy of slab s + 1 (issued one slab earlier) is awaited just
-    // before it, so that k-steps 2 and 3 can already fetch the first fragments of slab s + 1.
+    // before it, so that the second k-step can already fetch the first fragments of slab s + 1.
     // Epilogue operands are fetched where their latency is hidden.  Bias and gate of the tile's 128 columns:
     // one value per thread now, parked in LDS behind the slab buffers once the first slab's wait has passed.
     // (The gate row must be the same for all rows of the tile; tiles that straddle samples read it from
@@ -202,7 +208,6 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     __builtin_amdgcn_s_barrier();
     if (nslab > 1) issue(1, 1);
     read_set(0, 0);
-    read_set(0, 1);
     constexpr bool GEGLU = EPI == EPI_GEGLU;
     [[maybe_unused]] const int q_cols = EPI == EPI_QKV && p.q_scale != 0.f ? p.heads * 64 : 0;   // columns of the q part that are scaled
     [[maybe_unused]] const float q_scale = p.q_scale;
@@ -238,23 +243,23 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
         constexpr int STG = decltype(stage_tag)::value;
         if (s == nslab - 1) load_res(0);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; kk++) {
-            if (kk == 2 && s + 1 < nslab) {
+        for (int ks = 0; ks < BK / 32; ks++) {
+            if (ks == 1 && s + 1 < nslab) {
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // this wave's share of slab s + 1 has landed
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ... and its reads of slab s are complete
                 __builtin_amdgcn_s_barrier();
                 if (s + 2 < nslab) issue(s + 2, STG);
             }
-            if (kk < 2) read_set(STG, kk + 2);
-            else if (s + 1 < nslab) read_set(STG ^ 1, kk - 2);
+            if (ks == 0) read_set(STG, 1);
+            else if (s + 1 < nslab) read_set(STG ^ 1, 0);
 #pragma unroll
-            for (int fn = 0; fn < 2; fn++)
+            for (int fi = 0; fi < 4; fi++)
 #pragma unroll
-                for (int tm = 0; tm < TMW; tm++)
-                    acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[kk][fn], af[kk][tm], acc[fn][tm], 0, 0, 0);
+                for (int ti = 0; ti < TT; ti++)
+                    acc[fi][ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[ks][fi], af[ks][ti], acc[fi][ti], 0, 0, 0);
 #pragma unroll
-            for (int j = 0; j < 2 * TMW; j++) {   // fragment reads between the MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            for (int j = 0; j < 4 + TT; j++) {   // fragment reads between the MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x008, (4 * TT) / (4 + TT), 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
         }
@@ -267,7 +272,7 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     __builtin_amdgcn_s_barrier();                          // every wave is done with the slab buffers
 
     // ---- epilogue: registers -> LDS staging tile -> row-contiguous global stores -------------------
-    // Register i of tile (fn, tm): feature = wf*64 + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*32*TMW + tm*32 + lr.
+    // Register i of tile (fi, ti): feature = wf*64 + fi*16 + 4 q4 + i, token = wt*32*TMW + ti*16 + l16.
 #pragma unroll
     for (int pass = 0; pass < NPASS; pass++) {
         // Staging; GATE_LDS: the gate values come from LDS (always, unless the tile's rows straddle gate rows).
@@ -276,55 +281,49 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
         [[maybe_unused]] const size_t gate_stride = p.gate_stride;
         auto stage = [&, gate_ptr, gate_rows, gate_stride](auto gate_lds_tag) {
             constexpr bool GATE_LDS = decltype(gate_lds_tag)::value;
-            // bias (and gate) of this lane's 8 column groups first, in one batch of LDS reads
-            f32x4 bv[2][4];
-            [[maybe_unused]] f32x4 gv[2][4];
+            // bias (and gate) of this lane's 4 column groups first, in one batch of LDS reads
+            f32x4 bv[4];
+            [[maybe_unused]] f32x4 gv[4];
 #pragma unroll
-            for (int fn = 0; fn < 2; fn++)
+            for (int fi = 0; fi < 4; fi++) {
+                const int fl = wf * 64 + fi * 16 + 4 * q4;
+                bv[fi] = *reinterpret_cast<const f32x4*>(vec_lds + fl);
+                if constexpr (RES && GATE_LDS) gv[fi] = *reinterpret_cast<const f32x4*>(vec_lds + BN + fl);
+            }
 #pragma unroll
-                for (int gi = 0; gi < 4; gi++) {
-                    const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;
-                    bv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + fl);
-                    if constexpr (RES && GATE_LDS) gv[fn][gi] = *reinterpret_cast<const f32x4*>(vec_lds + BN + fl);
-                }
-#pragma unroll
-            for (int tm = 0; tm < TMW; tm++) {
-                const int trow = (NPASS == 1 ? wt * 32 * TMW : 0) + tm * 32 + lr;   // row inside the staging tile
+            for (int ti = 0; ti < TT; ti++) {
+                const int trow = (NPASS == 1 ? wt * 32 * TMW : 0) + ti * 16 + l16;   // row inside the staging tile
                 if constexpr (RES && !GATE_LDS) {
-                    const int r = row0 + wt * 32 * TMW + tm * 32 + lr;              // global token row
+                    const int r = row0 + wt * 32 * TMW + ti * 16 + l16;              // global token row
                     const float* gate_row = gate_ptr + (size_t)(min(r, m - 1) / gate_rows) * gate_stride;
 #pragma unroll
-                    for (int fn = 0; fn < 2; fn++)
-#pragma unroll
-                        for (int gi = 0; gi < 4; gi++)   // column clamped: masked on store
-                            gv[fn][gi] = *reinterpret_cast<const f32x4*>(gate_row + min(col0 + wf * 64 + fn * 32 + 8 * gi + 4 * hi, n - 4));
+                    for (int fi = 0; fi < 4; fi++)   // column clamped: masked on store
+                        gv[fi] = *reinterpret_cast<const f32x4*>(gate_row + min(col0 + wf * 64 + fi * 16 + 4 * q4, n - 4));
                 }
 #pragma unroll
-                for (int fn = 0; fn < 2; fn++)
+                for (int fi = 0; fi < 4; fi++) {
+                    const int fl = wf * 64 + fi * 16 + 4 * q4;      // feature inside the tile
+                    f32x4 v = acc[fi][ti];
+                    v += bv[fi];
+                    if constexpr (EPI == EPI_GELU_TANH) {
 #pragma unroll
-                    for (int gi = 0; gi < 4; gi++) {
-                        const int fl = wf * 64 + fn * 32 + 8 * gi + 4 * hi;      // feature inside the tile
-                        f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
-                        v += bv[fn][gi];
-                        if constexpr (EPI == EPI_GELU_TANH) {
+                        for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
+                    } else if constexpr (EPI == EPI_SILU) {
 #pragma unroll
-                            for (int j = 0; j < 4; j++) v[j] = gelu_tanh_f(v[j]);
-                        } else if constexpr (EPI == EPI_SILU) {
-#pragma unroll
-                            for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
-                        } else if constexpr (EPI == EPI_GATE_RES) {
-                            v *= gv[fn][gi];
-                        } else if constexpr (EPI == EPI_QKV) {
-                            if (col0 + fl < q_cols) v *= q_scale;      // the four features of v lie in one head
-                        }
-                        unsigned char* dst = smem + trow * STRIDE + fl * SE;
-                        if constexpr (F32OUT) {
-                            *reinterpret_cast<f32x4*>(dst) = v;
-                        } else {
-                            bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-                            *reinterpret_cast<bf16x4*>(dst) = o;
-                        }
+                        for (int j = 0; j < 4; j++) v[j] = silu_f(v[j]);
+                    } else if constexpr (EPI == EPI_GATE_RES) {
+                        v *= gv[fi];
+                    } else if constexpr (EPI == EPI_QKV) {
+                        if (col0 + fl < q_cols) v *= q_scale;      // the four features of v lie in one head
                     }
+                    unsigned char* dst = smem + trow * STRIDE + fl * SE;
+                    if constexpr (F32OUT) {
+                        *reinterpret_cast<f32x4*>(dst) = v;
+                    } else {
+                        bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+                        *reinterpret_cast<bf16x4*>(dst) = o;
+                    }
+                }
             }
         };
         if (NPASS == 1 || wt == pass) {
