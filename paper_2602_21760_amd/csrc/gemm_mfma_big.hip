@@ -1,23 +1,24 @@
 // Large-tile bf16 MFMA GEMM for gfx950: the same contraction as gemm_mfma.hip (out = epilogue(A W^T + bias),
 // A [m, k] tokens x features-in, W [n, k] features-out x features-in, fp32 accumulation in
-// v_mfma_f32_32x32x16_bf16, k in slabs of 64, identical order of accumulation, so a token's result has the
+// v_mfma_f32_16x16x32_bf16, k in slabs of 64, identical order of accumulation, so a token's result has the
 // same bits whichever of the two kernels computes it), for long-k launches with enough 256 x 128 tiles for the chip.
 //
 // Why a second geometry.  With 128 x 128 tiles, two workgroups per CU, a launch of 420 tiles and 96 k-slabs (the
 // SD3-shaped fc2: n = 1536, k = 6144) is one round in which 164 CUs carry two tiles and 92 carry one, every tile pays
 // for 64 KB of operand copies per CU and k-slab pair, and all tiles read their residual and write their output at
 // the same moment.  Here a workgroup of 4 waves (2 x 2) owns a 256 x 128 tile alone on its CU (216 tiles for the
-// same launch): a wave owns 128 x 64 outputs = 4 x 2 MFMA tiles (128 accumulator registers); per k-slab the CU copies
-// 48 KB for the same MFMA work, and a wave reads 0.75 KB of fragments per MFMA instead of 1 KB.  One wave per SIMD is
+// same launch): a wave owns 128 x 64 outputs = 8 x 4 MFMA tiles of 16 x 16 (128 accumulator registers); per k-slab the CU
+// copies 48 KB for the same MFMA work, and a wave reads three quarters of the fragment bytes per multiply-add.  One wave per SIMD is
 // enough for the MFMA pipe as long as nothing stands in front of its MFMAs in program order (a wave issues in order):
 // fragment reads AND slab copies are spread between the MFMAs, the copies of a slab over a whole slab period (a
-// quarter per k-step), so that the CU's copy path, which takes about 16 clocks per 1 KB request, never queues up.
+// quarter per half-step), so that the CU's copy path, which takes about 16 clocks per 1 KB request, never queues up.
 //
 // Main loop: as in gemm_mfma.hip (direct-to-LDS 16-byte buffer loads with the slab offset as the scalar
 // operand, XOR-swizzled unpadded 128-byte rows, explicit vmcnt / lgkmcnt waits and ONE raw barrier per slab), with
 // THREE slab buffers (a copy is in flight for one to two slab periods: a lone workgroup has no neighbour on its CU to
-// fill a stall) and the fragments of a k-step in two register sets: the reads of k-step j + 1 are issued between the
-// MFMAs of k-step j, across the slab boundary.  The slab buffers are separate arrays, so that the compiler knows
+// fill a stall).  A k-step of 32 is taken in two halves of four token tiles (16 MFMAs each), so a slab is four
+// half-steps; the token fragments of a half-step and the weight fragments of a k-step live in two register sets each, and
+// the reads of half-step j + 1 are issued between the MFMAs of half-step j, across the slab boundary.  The slab buffers are separate arrays, so that the compiler knows
 // that a copy into one and a fragment read from another do not alias and interleaves them freely.
 //
 // Epilogue: every wave stages its own 32-token x 64-feature pieces through its own part of the slab buffers (no
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     const int tid = threadIdx.x, lane = tid % 64;
     const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
     const int wt = wave % 2, wf = wave / 2;          // wave position: tokens, features
-    const int lr = lane % 32, hi = lane / 32;
+    const int l16 = lane % 16, q4 = lane / 16;      // MFMA 16x16x32: row / column of the lane, its quarter of the 32 k
 
     // Slab copies: chunk c of this wave covers stage rows 8 (wave + 4 c) .. + 7 (rows 0 .. BM-1 = A, then BN rows
     // of W); lane i fills 16-byte slot i % 8 of row i / 8 with k-vector (slot ^ swz(row)).  Rows past the end are
@@ -154,27 +155,39 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     // Accumulators [feature tile][token tile].  They are never zeroed in registers: the first k-step of the first
     // slab multiplies into a constant-zero C operand (an accumulator file of 256 registers initialised through
     // vector registers would evict every long-lived address of the main loop).
-    f32x16 acc[TFW][TMW];
+    constexpr int FT = 2 * TFW, TT = 2 * TMW;      // MFMA tiles of 16 features / 16 tokens per wave
+    static_assert(TT % 2 == 0 && TT / 2 == 4, "a k-step is taken in two halves of four token tiles");
+    f32x4 acc[FT][TT];
 
-    // Fragment addresses inside a stage: with the swizzle the 16-byte slot of the read for k-step kk of MFMA tile
-    // t is (lane part) ^ 2 (kk ^ 2 t), so four per-lane bases per operand cover all reads and the tile's row block
-    // (32 t rows) is an immediate offset (the waves' own row offsets are multiples of 64 and leave the swizzle alone).
-    const int lb = (hi ^ lr ^ (lr >> 3)) & 7;
+    // Fragment addresses inside a stage.  A fragment of v_mfma_f32_16x16x32_bf16 is 16 rows x 32 k: lane (l16, q4) reads
+    // the 16 bytes of row l16 that hold k = 32 ks + 8 q4 .. + 7, i.e. slot 4 ks + q4 of the row; with the swizzle and tile
+    // rows 16 t + l16 that slot sits at (lane part) ^ (4 ks ^ 2 (t % 4)), so four per-lane bases per operand cover all
+    // reads and the tile's row block (16 t rows) is an immediate offset (the waves' own row offsets are multiples of 64
+    // and leave the swizzle alone).
+    const int lb = (q4 ^ (l16 & 7) ^ (l16 >> 3)) & 7;
     int a_base[4], w_base[4];
 #pragma unroll
     for (int c = 0; c < 4; c++) {
-        a_base[c] = (wt * 32 * TMW + lr) * ROWB + ((lb ^ (2 * c)) * 16);
-        w_base[c] = BM * ROWB + (wf * 32 * TFW + lr) * ROWB + ((lb ^ (2 * c)) * 16);
+        a_base[c] = (wt * 32 * TMW + l16) * ROWB + ((lb ^ (2 * c)) * 16);
+        w_base[c] = BM * ROWB + (wf * 32 * TFW + l16) * ROWB + ((lb ^ (2 * c)) * 16);
     }
-    bf16x8 af[2][TMW], wfr[2][TFW];
-    auto read_set = [&](int stage, int kk, int set) {
+    // A k-step of 32 is taken in two halves of four token tiles each (16 MFMAs): half-step hs = 2 ks + half of a slab
+    // uses the weight fragments of k-step ks (set ks % 2, read once per k-step) and the token fragments of its half
+    // (set hs % 2).  That keeps 32 + 32 fragment registers next to the 128 accumulators.
+    bf16x8 af[2][TT / 2], wfr[2][FT];
+    auto read_half = [&](int stage, int hs) {
         const unsigned char* base = stage_base(stage);
+        const int ks = hs >> 1, half = hs & 1;
 #pragma unroll
-        for (int t = 0; t < TMW; t++)
-            af[set][t] = *reinterpret_cast<const bf16x8*>(base + a_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+        for (int t = 0; t < TT / 2; t++) {
+            const int ti = half * (TT / 2) + t;
+            af[hs & 1][t] = *reinterpret_cast<const bf16x8*>(base + a_base[((2 * ks) ^ ti) & 3] + ti * 16 * ROWB);
+        }
+        if (half == 0) {
 #pragma unroll
-        for (int t = 0; t < TFW; t++)
-            wfr[set][t] = *reinterpret_cast<const bf16x8*>(base + w_base[(kk ^ (2 * t)) & 3] + t * 32 * ROWB);
+            for (int t = 0; t < FT; t++)
+                wfr[ks & 1][t] = *reinterpret_cast<const bf16x8*>(base + w_base[((2 * ks) ^ t) & 3] + t * 16 * ROWB);
+        }
     };
 
     // Epilogue operands where their latency hides: bias and gate of the tile's columns now (parked in LDS behind the
@@ -208,7 +221,7 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
         for (int j = 0; j < VPT; j++) vec_lds[tid + 256 * j] = val[j];
     }
     __builtin_amdgcn_s_barrier();
-    read_set(0, 0, 0);
+    read_half(0, 0);
 
     constexpr bool F32OUT = sizeof(OT) == 4;
     constexpr bool RES = EPI == EPI_GATE_RES;
@@ -244,33 +257,38 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
         }
     };
 
-    auto mfma_step = [&](int set, auto first_tag, auto copies_tag) {
+    // the 16 MFMAs of half-step hs; READS = fragment reads of the next half-step that are issued between them
+    auto mfma_half = [&](auto hs_tag, auto first_tag, auto copies_tag) {
+        constexpr int HS = decltype(hs_tag)::value;
         constexpr bool FIRST = decltype(first_tag)::value;
-        constexpr int COPIES = decltype(copies_tag)::value;      // slab copies issued next to this k-step
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        constexpr int COPIES = decltype(copies_tag)::value;      // slab copies issued next to this half-step
+        constexpr int READS = (HS & 1) ? TT / 2 + FT : TT / 2;   // the next half-step starts a k-step: weight fragments too
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int fn = 0; fn < TFW; fn++)
+        for (int fi = 0; fi < FT; fi++)
 #pragma unroll
-            for (int tm = 0; tm < TMW; tm++)
-                acc[fn][tm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[set][fn], af[set][tm], FIRST ? zero : acc[fn][tm], 0, 0, 0);
-        // the fragment reads of the next k-step (and, behind the barrier, the copies of the next free slab) between the MFMAs
-        if constexpr (COPIES > 0) interleave_reads_and_copies<0, TMW * TFW, TMW + TFW, COPIES>();
-        else interleave_reads<0, TMW + TFW, TMW * TFW>();
+            for (int t = 0; t < TT / 2; t++) {
+                const int ti = (HS & 1) * (TT / 2) + t;
+                acc[fi][ti] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfr[(HS >> 1) & 1][fi], af[HS & 1][t], FIRST ? zero : acc[fi][ti], 0, 0, 0);
+            }
+        // the fragment reads of the next half-step (and, behind the barrier, the copies of the next free slab) between the MFMAs
+        if constexpr (COPIES > 0) interleave_reads_and_copies<0, FT * TT / 2, READS, COPIES>();
+        else interleave_reads<0, READS, FT * TT / 2>();
     };
-    // Slab s sits in stage s % NST.  k-step kk uses fragment set kk % 2 and first requests the fragments of the next
-    // k-step.  ONE barrier per slab, before the reads of k-step 3 + 1 = k-step 0 of slab s + 1: by then this wave's
+    // Slab s sits in stage s % NST.  Half-step hs first requests the fragments of the next half-step.  ONE barrier per
+    // slab, before the reads of half-step 3 + 1 = half-step 0 of slab s + 1: by then this wave's
     // share of slab s + 1 has landed (vmcnt: only the copies of younger slabs may be outstanding) and its reads of
     // slab s are complete (lgkmcnt), so behind the barrier slab s + 1 is readable and stage s % NST can be refilled
     // with slab s + NST.
-    constexpr int CQ = CPW / 4;                                // copies per k-step in the steady state
-    static_assert(CPW % 4 == 0, "a wave's copies of a slab are spread over the four k-steps");
+    constexpr int CQ = CPW / 4;                                // copies per half-step in the steady state
+    static_assert(CPW % 4 == 0, "a wave's copies of a slab are spread over the four half-steps");
     auto slab_step = [&](int s, auto stage_tag, auto first_tag, bool first_quarter_only) {
         constexpr int STG = decltype(stage_tag)::value;
         constexpr bool FIRST_SLAB = decltype(first_tag)::value;
         if (s == nslab - 1) load_res(0, 0);
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; kk++) {
-            if (kk < 3) read_set(STG, kk + 1, (kk + 1) & 1);
+        auto half = [&](auto hs_tag) {
+            constexpr int HS = decltype(hs_tag)::value;
+            if constexpr (HS < 3) read_half(STG, HS + 1);
             else if (s + 1 < nslab) {
                 if (NST > 2 && s + 2 < nslab) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * CPW) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -280,38 +298,42 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
                     if (first_quarter_only) issue_chunks(s + NST, STG, std::integral_constant<int, 0>{}, std::integral_constant<int, CQ>{});
                     else issue(s + NST, STG);
                 }
-                read_set((STG + 1) % NST, 0, 0);
+                read_half((STG + 1) % NST, 0);
             }
-            if (FIRST_SLAB && kk == 0) mfma_step(0, std::true_type{}, std::integral_constant<int, 0>{});
-            else mfma_step(kk & 1, std::false_type{}, std::integral_constant<int, 0>{});
-        }
+            if constexpr (FIRST_SLAB && HS < 2) mfma_half(hs_tag, std::true_type{}, std::integral_constant<int, 0>{});
+            else mfma_half(hs_tag, std::false_type{}, std::integral_constant<int, 0>{});
+        };
+        half(std::integral_constant<int, 0>{});
+        half(std::integral_constant<int, 1>{});
+        half(std::integral_constant<int, 2>{});
+        half(std::integral_constant<int, 3>{});
     };
     // Steady state (slab s + NST exists): no conditions, so that the copies requested behind the barrier are spread
-    // between the MFMAs of the same k-step instead of standing in front of them (a wave issues in order: sixteen
+    // between the MFMAs of the same half-step instead of standing in front of them (a wave issues in order: sixteen
     // copy instructions in a row hold up the MFMAs behind them while the matrix pipe runs dry).
-    // The copies of a slab are spread over four k-steps (a quarter each), so that the copy path of the CU sees an even
+    // The copies of a slab are spread over four half-steps (a quarter each), so that the copy path of the CU sees an even
     // stream instead of a burst per slab: the first quarter of slab s + NST behind the barrier of slab s (which frees
-    // its buffer), the other three next to k-steps 0 .. 2 of slab s + 1.  On entry the first quarter of slab
+    // its buffer), the other three next to half-steps 0 .. 2 of slab s + 1.  On entry the first quarter of slab
     // s + NST - 1 has been requested, its other quarters not.  The count of the wait is unchanged: the copies younger
     // than those of slab s + 1 are the CPW copies of slab s + 2.
     static_assert(NST == 3, "the steady state below is written for three slab buffers");
     auto slab_step_mid = [&](int s, auto stage_tag) {
         constexpr int STG = decltype(stage_tag)::value;
-        read_set(STG, 1, 1);
+        read_half(STG, 1);
         issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, CQ>{}, std::integral_constant<int, 2 * CQ>{});
-        mfma_step(0, std::false_type{}, std::integral_constant<int, CQ>{});
-        read_set(STG, 2, 0);
+        mfma_half(std::integral_constant<int, 0>{}, std::false_type{}, std::integral_constant<int, CQ>{});
+        read_half(STG, 2);
         issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, 2 * CQ>{}, std::integral_constant<int, 3 * CQ>{});
-        mfma_step(1, std::false_type{}, std::integral_constant<int, CQ>{});
-        read_set(STG, 3, 1);
+        mfma_half(std::integral_constant<int, 1>{}, std::false_type{}, std::integral_constant<int, CQ>{});
+        read_half(STG, 3);
         issue_chunks(s + NST - 1, (STG + NST - 1) % NST, std::integral_constant<int, 3 * CQ>{}, std::integral_constant<int, CPW>{});
-        mfma_step(0, std::false_type{}, std::integral_constant<int, CQ>{});
+        mfma_half(std::integral_constant<int, 2>{}, std::false_type{}, std::integral_constant<int, CQ>{});
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NST - 2) * CPW) : "memory");
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
-        read_set((STG + 1) % NST, 0, 0);
+        read_half((STG + 1) % NST, 0);
         issue_chunks(s + NST, STG, std::integral_constant<int, 0>{}, std::integral_constant<int, CQ>{});
-        mfma_step(1, std::false_type{}, std::integral_constant<int, CQ>{});
+        mfma_half(std::integral_constant<int, 3>{}, std::false_type{}, std::integral_constant<int, CQ>{});
     };
     const bool steady = 2 * NST < nslab;                    // the steady-state loop below runs at least once
     slab_step(0, std::integral_constant<int, 0>{}, std::true_type{}, steady);
@@ -332,7 +354,8 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     __builtin_amdgcn_s_barrier();                          // every wave is done with the slab buffers
 
     // ---- epilogue: per wave, registers -> its own LDS staging piece -> row-contiguous global stores --------
-    // Register i of tile (fn, tm): feature = wf*WCOLS + fn*32 + 8 (i / 4) + 4 hi + i % 4, token = wt*32*TMW + tm*32 + lr.
+    // Register i of tile (fi, ti): feature = wf*WCOLS + fi*16 + 4 q4 + i, token = wt*32*TMW + ti*16 + l16; piece tm of 32
+    // tokens is the pair of token tiles 2 tm, 2 tm + 1.
     // staging area of wave w: with two slab buffers half a buffer each, with three the first 36 KB of buffers 0, 1, 2 and
     // the remaining 12 KB of buffer 0
     unsigned char* stg = NST == 2 ? stage_base(wave & 1) + (wave >> 1) * (STAGE_BYTES / 2)
@@ -350,11 +373,12 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
         auto stage = [&](auto gate_lds_tag) {
             constexpr bool GATE_LDS = decltype(gate_lds_tag)::value;
 #pragma unroll
-            for (int fn = 0; fn < TFW; fn++)
+            for (int fi = 0; fi < FT; fi++)
 #pragma unroll
-                for (int gi = 0; gi < 4; gi++) {
-                    const int fl = fn * 32 + 8 * gi + 4 * hi;      // feature inside the wave's columns
-                    f32x4 v = {acc[fn][tm][4 * gi], acc[fn][tm][4 * gi + 1], acc[fn][tm][4 * gi + 2], acc[fn][tm][4 * gi + 3]};
+                for (int h2 = 0; h2 < 2; h2++) {
+                    const int fl = fi * 16 + 4 * q4;               // feature inside the wave's columns
+                    const int prow = h2 * 16 + l16;                // token inside the 32-token piece
+                    f32x4 v = acc[fi][2 * tm + h2];
                     v += *reinterpret_cast<const f32x4*>(vec_lds + wf * WCOLS + fl);
                     if constexpr (EPI == EPI_GELU_TANH) {
 #pragma unroll
@@ -366,12 +390,12 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
                         if constexpr (GATE_LDS) {
                             v *= *reinterpret_cast<const f32x4*>(vec_lds + BN + wf * WCOLS + fl);
                         } else {
-                            const int r = wrow0 + tm * 32 + lr;    // global token row; column clamped: masked on store
+                            const int r = wrow0 + tm * 32 + prow;  // global token row; column clamped: masked on store
                             const float* gate_row = gate_ptr + (size_t)(min(r, m - 1) / gate_rows) * gate_stride;
                             v *= *reinterpret_cast<const f32x4*>(gate_row + min(wcol0 + fl, n - 4));
                         }
                     }
-                    unsigned char* dst = stg + lr * STRIDE + fl * SE;
+                    unsigned char* dst = stg + prow * STRIDE + fl * SE;
                     if constexpr (F32OUT) {
                         *reinterpret_cast<f32x4*>(dst) = v;
                     } else {
