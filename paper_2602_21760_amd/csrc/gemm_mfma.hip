@@ -16,7 +16,7 @@
 // of LDS per instruction, no VGPR staging, no ds_write; the slab's byte offset is the scalar operand and the
 // per-lane offsets are loop invariants, so a slab costs no vector address arithmetic), double buffered: the copy
 // of slab s + 1 runs while slab s is multiplied.  LDS rows are unpadded; the 16-byte slots of a row are XOR-swizzled
-// with (row ^ row >> 3) & 7 so that the 16-byte fragment reads of 8 consecutive rows hit distinct
+// with (row ^ row >> 3) & 7 so that the 16-byte fragment reads that are served together hit distinct
 // banks (the swizzle is applied on the global side: each lane picks which 16 bytes it fetches).
 // Waits on the copies are explicit (s_waitcnt vmcnt + s_barrier); a full __syncthreads() would
 // force vmcnt(0) on every barrier through its fence.  The fragments of the two k-steps (of 32) of a
@@ -151,12 +151,16 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
 #pragma unroll
             for (int i = 0; i < 4; i++) acc[fi][ti][i] = 0.f;
 
-    // Fragment addresses inside a stage.  A fragment of v_mfma_f32_16x16x32_bf16 is 16 rows x 32 k: lane (l16, q4) reads
-    // the 16 bytes of row l16 that hold k = 32 ks + 8 q4 .. + 7, i.e. 16-byte slot 4 ks + q4 of the row.  With the XOR
-    // swizzle and tile rows 16 t + l16 that slot sits at (lane part) ^ (4 ks ^ 2 t): four per-lane bases per operand
-    // cover all the reads of a slab, and the tile row block (t * 16 rows) is an immediate offset.  (With 32 token rows per
-    // wave the wave's own row offset 32 wt also reaches bit 2 of the swizzle; it is folded into the lane part.)
-    const int lb = (q4 ^ (l16 & 7) ^ (l16 >> 3)) & 7;
+    // Fragment addresses inside a stage.  A fragment of v_mfma_f32_16x16x32_bf16 is 16 rows x 32 k, lane (l16, q4)
+    // holding 8 k of row l16.  Which 8 is free as long as both operands agree (the order of the contraction index
+    // inside an MFMA does not matter to the product): lane quarter q4 takes the 16-byte slot 4 ks + (q4 >> 1 | (q4 & 1) << 1)
+    // of its row, so that lanes i and i + 32 read adjacent slots of one row, 32 contiguous bytes.  (With slot 4 ks + q4
+    // the same reads take twice as long: the LDS counters show four conflict cycles per read, whatever the swizzle.)
+    // With the XOR swizzle and tile rows 16 t + l16 the slot sits at (lane part) ^ (4 ks ^ 2 t): four per-lane bases per
+    // operand cover all the reads of a slab, and the tile row block (t * 16 rows) is an immediate offset.  (With 32
+    // token rows per wave the wave's own row offset 32 wt also reaches bit 2 of the swizzle; it is folded into the lane part.)
+    const int kq = (q4 >> 1) | ((q4 & 1) << 1);
+    const int lb = (kq ^ (l16 & 7) ^ (l16 >> 3)) & 7;
     const int lb_a = TMW == 1 ? lb ^ (4 * wt) : lb;
     int a_base[4], w_base[4];
 #pragma unroll

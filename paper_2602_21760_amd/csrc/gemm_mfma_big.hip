@@ -159,12 +159,14 @@ __global__ __launch_bounds__(256, 1) void gemm_big_kernel(GemmGroup g, int tiles
     static_assert(TT % 2 == 0 && TT / 2 == 4, "a k-step is taken in two halves of four token tiles");
     f32x4 acc[FT][TT];
 
-    // Fragment addresses inside a stage.  A fragment of v_mfma_f32_16x16x32_bf16 is 16 rows x 32 k: lane (l16, q4) reads
-    // the 16 bytes of row l16 that hold k = 32 ks + 8 q4 .. + 7, i.e. slot 4 ks + q4 of the row; with the swizzle and tile
-    // rows 16 t + l16 that slot sits at (lane part) ^ (4 ks ^ 2 (t % 4)), so four per-lane bases per operand cover all
-    // reads and the tile's row block (16 t rows) is an immediate offset (the waves' own row offsets are multiples of 64
-    // and leave the swizzle alone).
-    const int lb = (q4 ^ (l16 & 7) ^ (l16 >> 3)) & 7;
+    // Fragment addresses inside a stage, as in gemm_mfma.hip: lane (l16, q4) of a 16 x 16 x 32 fragment reads the 16-byte
+    // slot 4 ks + (q4 >> 1 | (q4 & 1) << 1) of row l16 (lanes i and i + 32 read 32 contiguous bytes; both operands use the
+    // same assignment of k to lane quarters, so the accumulation order equals that of the 128 x 128 kernel); with the
+    // swizzle and tile rows 16 t + l16 the slot sits at (lane part) ^ (4 ks ^ 2 (t % 4)), so four per-lane bases per
+    // operand cover all reads and the tile's row block (16 t rows) is an immediate offset (the waves' own row offsets are
+    // multiples of 64 and leave the swizzle alone).
+    const int kq = (q4 >> 1) | ((q4 & 1) << 1);
+    const int lb = (kq ^ (l16 & 7) ^ (l16 >> 3)) & 7;
     int a_base[4], w_base[4];
 #pragma unroll
     for (int c = 0; c < 4; c++) {
