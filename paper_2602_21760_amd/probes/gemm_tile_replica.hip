@@ -2,11 +2,12 @@
 //
 // A workgroup of 4 waves (64 x 64 outputs each) runs the k loop of gemm_mfma_kernel over its tile: k-slabs of 64 copied
 // global -> LDS by 16-byte direct-to-LDS buffer loads into two stages (same chunking, swizzle and waits), four k-steps per
-// slab with two fragment reads per operand and four v_mfma_f32_32x32x16_bf16 each, one barrier per slab; no bias, no
-// epilogue (one float per thread is stored so that nothing is optimised away).  1024 tiles are exactly two rounds of the
+// slab with two fragment reads per operand and a quarter of the slab's multiply-adds each, one barrier per slab; no
+// bias, no epilogue (one float per thread is stored so that nothing is optimised away).  The MFMAs are either
+// v_mfma_f32_16x16x32_bf16, the form the kernels use, or v_mfma_f32_32x32x16_bf16, the form they used before, on the same
+// fragment reads and with the same number of multiply-adds.  1024 tiles are exactly two rounds of the
 // chip's 512 workgroup slots, 512 tiles one round.  Variants leave out the copies (after the first two slabs), the fragment
-// reads (operands stay in registers), or both, and replace the MFMAs by the 16x16x32 form with the same fragment reads and
-// the same number of multiply-adds; operands are one constant or roughly normal random bf16 (the clock that the chip's
+// reads (operands stay in registers), or both; operands are one constant or roughly normal random bf16 (the clock that the chip's
 // power management grants depends on how many bits toggle).
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -109,26 +110,27 @@ __global__ __launch_bounds__(256, 2) void k(const bf16_t* A, const bf16_t* W, fl
     for (int i = 0; i < 4; i++) for (int j = 0; j < 4; j++) for (int e = 0; e < 4; e++) r += acc4[i][j][e];
     out[(size_t)blockIdx.x * 256 + tid] = r;
 }
-template <int FLAGS> void run(const char* name, const bf16_t* A, const bf16_t* W, float* out, int m, int n, int kdim, const char* data) {
+// One measurement: 100 launches back to back between one pair of events, after 5 untimed ones; microseconds per launch.
+template <int FLAGS> float run(const bf16_t* A, const bf16_t* W, float* out, int m, int n, int kdim) {
     hipEvent_t e0, e1; CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
     const int tiles_n = n / BN, tiles = (m / BM) * tiles_n;
     for (int rep = 0; rep < 5; rep++) k<FLAGS><<<tiles, 256>>>(A, W, out, m, n, kdim, tiles_n);
     float ms = 0;
-    const int reps = 40;      // back to back, one pair of events around all of them
+    const int reps = 100;
     CK(hipEventRecord(e0));
     for (int rep = 0; rep < reps; rep++) k<FLAGS><<<tiles, 256>>>(A, W, out, m, n, kdim, tiles_n);
     CK(hipEventRecord(e1));
     CK(hipEventSynchronize(e1));
     CK(hipEventElapsedTime(&ms, e0, e1));
-    ms /= reps;
-    printf("| %s | %s | %d x %d x %d | %d | %.1f | %.0f |\n", data, name, m, n, kdim, tiles, ms * 1e3, 2.0 * m * n * kdim / (ms * 1e-3) * 1e-12);
+    CK(hipEventDestroy(e0)); CK(hipEventDestroy(e1));
+    return ms * 1e3f / reps;
 }
 int main() {
     const int MMAX = 8192, NMAX = 6144, K = 1536;
     bf16_t *A, *W; float* out;
     CK(hipMalloc(&A, (size_t)MMAX * K * 2)); CK(hipMalloc(&W, (size_t)NMAX * K * 2)); CK(hipMalloc(&out, (size_t)4096 * 256 * 4));
     unsigned short* h = (unsigned short*)malloc((size_t)MMAX * K * 2);
-    printf("| operands | variant | m x n x k | tiles | us per launch (40 back to back) | TFLOP/s |\n|---|---|---|---|---|---|\n");
+    printf("| operands | variant | m x n x k | tiles | us per launch (median of 3 x 100 back to back) | TFLOP/s |\n|---|---|---|---|---|---|\n");
     for (int random = 0; random < 2; random++) {
         unsigned st = 777u;
         for (size_t i = 0; i < (size_t)MMAX * K; i++) { float acc = 0; for (int r = 0; r < 4; r++) { st = st * 1664525u + 1013904223u; acc += (st >> 8) * (1.0f / 16777216.0f); } float x = random ? (acc - 2.0f) * 1.7f : 0.0625f; unsigned u; memcpy(&u, &x, 4); h[i] = (unsigned short)(u >> 16); }
@@ -136,13 +138,27 @@ int main() {
         CK(hipMemcpy(W, h, (size_t)NMAX * K * 2, hipMemcpyHostToDevice));
         const char* d = random ? "random" : "constant";
         // 1024 tiles = exactly two rounds of 512 slots; 512 tiles = one round
-        run<0>("as the kernel", A, W, out, 4096, 4096, K, d);
-        run<0>("as the kernel", A, W, out, 2048, 4096, K, d);
-        run<F_NOCOPY>("without the copies", A, W, out, 4096, 4096, K, d);
-        run<F_NOLDS>("without the fragment reads", A, W, out, 4096, 4096, K, d);
-        run<F_NOCOPY | F_NOLDS>("MFMAs only", A, W, out, 4096, 4096, K, d);
-        run<F_SMALL>("16x16x32 MFMAs", A, W, out, 4096, 4096, K, d);
-        run<F_SMALL | F_NOCOPY | F_NOLDS>("16x16x32 MFMAs only", A, W, out, 4096, 4096, K, d);
+        // The variants are measured in turn, three times over (the clock the chip grants drifts over milliseconds, so a
+        // variant must not always follow the same neighbour); the median of the three is printed.
+        const char* names[8] = {"main loop, 16x16x32 MFMAs", "main loop, 16x16x32 MFMAs, one round", "... without the copies", "... without the fragment reads",
+                                "... MFMAs only", "main loop, 32x32x16 MFMAs", "... without the copies", "... MFMAs only"};
+        const int ms_[8] = {4096, 2048, 4096, 4096, 4096, 4096, 4096, 4096};
+        float us[8][3];
+        for (int pass = 0; pass < 3; pass++) {
+            us[0][pass] = run<F_SMALL>(A, W, out, 4096, 4096, K);
+            us[5][pass] = run<0>(A, W, out, 4096, 4096, K);
+            us[1][pass] = run<F_SMALL>(A, W, out, 2048, 4096, K);
+            us[2][pass] = run<F_SMALL | F_NOCOPY>(A, W, out, 4096, 4096, K);
+            us[6][pass] = run<F_NOCOPY>(A, W, out, 4096, 4096, K);
+            us[3][pass] = run<F_SMALL | F_NOLDS>(A, W, out, 4096, 4096, K);
+            us[4][pass] = run<F_SMALL | F_NOCOPY | F_NOLDS>(A, W, out, 4096, 4096, K);
+            us[7][pass] = run<F_NOCOPY | F_NOLDS>(A, W, out, 4096, 4096, K);
+        }
+        for (int v = 0; v < 8; v++) {
+            float a = us[v][0], b = us[v][1], c = us[v][2];
+            const float med = a > b ? (b > c ? b : (a > c ? c : a)) : (a > c ? a : (b > c ? c : b));
+            printf("| %s | %s | %d x 4096 x %d | %d | %.1f | %.0f |\n", d, names[v], ms_[v], K, ms_[v] / BM * (4096 / BN), med, 2.0 * ms_[v] * 4096.0 * K / (med * 1e-6) * 1e-12);
+        }
     }
     CK(hipDeviceSynchronize());
     return 0;
