@@ -40,12 +40,13 @@ constexpr int PAIRS = 64;                  // pairs in the global buffer (each 2
 
 __device__ __forceinline__ int swz_v(int r) { return ((r >> 1) & 1) * 4; }
 
-enum : int { F_LDS = 1, F_ORDER = 2, F_BARRIER = 4, F_COPY = 8, F_NO_EXP = 16 };
+enum : int { F_LDS = 1, F_ORDER = 2, F_BARRIER = 4, F_COPY = 8, F_NO_EXP = 16, F_SMALL = 32 };
 
 // flags: see the enum; blockDim = 256 (F_BARRIER: one workgroup of 4 waves, several per CU) or 256 x waves per SIMD
 template <int FLAGS>
 __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const unsigned char* kv, int random_regs) {
     constexpr bool LDS = FLAGS & F_LDS, ORDER = FLAGS & F_ORDER, BAR = FLAGS & F_BARRIER, COPY = FLAGS & F_COPY, NO_EXP = FLAGS & F_NO_EXP;
+    constexpr bool SMALL = FLAGS & F_SMALL;      // the same fragments multiplied by twice as many v_mfma_f32_16x16x32_bf16 (same multiply-adds)
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];      // two buffers of a K and a V tile
     for (int i = threadIdx.x; i < 4 * TILE / 4; i += blockDim.x) reinterpret_cast<unsigned*>(smem)[i] = reinterpret_cast<const unsigned*>(kv)[i];
     __syncthreads();
@@ -79,6 +80,10 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
     f32x16 o[2];
     for (int d = 0; d < 2; d++)
         for (int i = 0; i < 16; i++) o[d][i] = 0.f;
+    f32x4 o4[SMALL ? 8 : 1];
+    if constexpr (SMALL)
+        for (int d = 0; d < 8; d++)
+            for (int i = 0; i < 4; i++) o4[d][i] = 0.f;
     float l = 0.f;
     const bf16x2 ones = {(bf16_t)1.0f, (bf16_t)1.0f};
 
@@ -99,6 +104,10 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
         }
         f32x16 s[2];
         for (int i = 0; i < 16; i++) s[0][i] = s[1][i] = 0.f;
+        f32x4 s4[SMALL ? 8 : 1];
+        if constexpr (SMALL)
+            for (int d = 0; d < 8; d++)
+                for (int i = 0; i < 4; i++) s4[d][i] = 0.f;
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             bf16x8 kf = a[j & 3];
@@ -106,7 +115,10 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
                 const int kt = j & 1, kk = j >> 1;
                 kf = *reinterpret_cast<const bf16x8*>(kbase[(kk ^ (2 * kt)) & 3] + boff + kt * 32 * 128);
             }
-            s[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q[j >> 1], s[j & 1], 0, 0, 0);
+            if constexpr (SMALL) {
+                s4[j & 3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, q[j >> 1], s4[j & 3], 0, 0, 0);
+                s4[4 + (j & 3)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, q[(j >> 1) ^ 1], s4[4 + (j & 3)], 0, 0, 0);
+            } else s[j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, q[j >> 1], s[j & 1], 0, 0, 0);
         }
         if (ORDER) __builtin_amdgcn_sched_barrier(0);
         bf16x4 vh[2][2][2][2];
@@ -126,7 +138,12 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = NO_EXP ? (bf16_t)s[kt][i] : (bf16_t)__builtin_amdgcn_exp2f(s[kt][i]);
+            for (int i = 0; i < 16; i++) {
+                float sc;
+                if constexpr (SMALL) sc = s4[4 * kt + i / 4][i % 4];
+                else sc = s[kt][i];
+                pb[kt][i / 8][i % 8] = NO_EXP ? (bf16_t)sc : (bf16_t)__builtin_amdgcn_exp2f(sc);
+            }
         if (ORDER) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 2; d++)
@@ -145,7 +162,10 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
                         const bf16x4 lo = vh[d][kt][hf][0], hi = vh[d][kt][hf][1];
                         vf = bf16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     }
-                    o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kt][hf], o[d], 0, 0, 0);
+                    if constexpr (SMALL) {
+                        o4[4 * d + 2 * kt + hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[kt][hf], o4[4 * d + 2 * kt + hf], 0, 0, 0);
+                        o4[4 * (d ^ 1) + 2 * kt + hf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[kt ^ 1][hf], o4[4 * (d ^ 1) + 2 * kt + hf], 0, 0, 0);
+                    } else o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[kt][hf], o[d], 0, 0, 0);
                 }
 #pragma unroll
         for (int kt = 0; kt < 2; kt++)
@@ -158,11 +178,17 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
                 }
         if ((it & 63) == 63)      // keep the accumulators bounded
             for (int d = 0; d < 2; d++)
-                for (int i = 0; i < 16; i++) o[d][i] *= 0.001f;
+                for (int i = 0; i < 16; i++) {
+                    if constexpr (SMALL) o4[4 * d + i / 4][i % 4] *= 0.001f;
+                    else o[d][i] *= 0.001f;
+                }
     }
     float r = l;
     for (int d = 0; d < 2; d++)
-        for (int i = 0; i < 16; i++) r += o[d][i];
+        for (int i = 0; i < 16; i++) {
+            if constexpr (SMALL) r += o4[4 * d + i / 4][i % 4];
+            else r += o[d][i];
+        }
     out[((size_t)blockIdx.x * 1024 + threadIdx.x) % (256 * 1024)] = r;
 }
 
@@ -287,6 +313,21 @@ int main() {
             row("... phases in program order", w, run<F_LDS | F_ORDER>(out, n, kv, random, w, cus));
             row("... 4-wave workgroups, barrier per tile", w, run<F_LDS | F_ORDER | F_BARRIER>(out, n, kv, random, w, cus));
             row("... tile copies global -> LDS", w, run<F_LDS | F_ORDER | F_BARRIER | F_COPY>(out, n, kv, random, w, cus));
+        }
+    }
+    // the complete tile with either MFMA form, random operands (still resident), 4 waves per SIMD: measured in turn, three
+    // times over, since the granted clock drifts over milliseconds; median
+    {
+        float ms[2][3];
+        for (int pass = 0; pass < 3; pass++) {
+            ms[0][pass] = run<F_LDS | F_ORDER | F_BARRIER | F_COPY>(out, n, kv, 1, 4, cus);
+            ms[1][pass] = run<F_LDS | F_ORDER | F_BARRIER | F_COPY | F_SMALL>(out, n, kv, 1, 4, cus);
+        }
+        const char* names[2] = {"complete tile, 32x32x16 MFMAs (median of 3, in turn)", "complete tile, 16x16x32 MFMAs (median of 3, in turn)"};
+        for (int v = 0; v < 2; v++) {
+            const float a = ms[v][0], b = ms[v][1], c = ms[v][2];
+            const float med = a > b ? (b > c ? b : (a > c ? c : a)) : (a > c ? a : (b > c ? c : b));
+            printf("| random | %s | 4 | %.3f | %.1f | %.0f |\n", names[v], med, med * 1e6 / ((double)n * 4), 16.0 * 32768.0 * 4.0 * cus * n * 4 / (med * 1e-3) * 1e-12);
         }
     }
     CK(hipDeviceSynchronize());
