@@ -452,11 +452,18 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 #undef HYB_KEY_LOOP
 
     const float l_tot[2] = {row_total(l_run[0]), row_total(l_run[1])};
+    // What the stores below need of the lane is derived here again, from a lane index the compiler cannot trace back
+    // (an empty asm statement): row numbers and output addresses computed ahead of the key loop would have to live
+    // through it in registers that the loop needs, or in scratch memory.
+    int lane_e = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+    asm volatile("" : "+v"(lane_e));
+    const int q4_e = lane_e / 16;
+    const int qrow_e = qb * BQ + wave * 32 + lane_e % 16;   // second row: + 16
     if (nparts > 1) {   // partial result of a split unit: merged by attention_merge_kernel
-        float* dst = a.part + ((size_t)unit * nparts + part) * PART_FLOATS + tid;
+        float* dst = a.part + ((size_t)unit * nparts + part) * PART_FLOATS + wave * 64 + lane_e;
 #pragma unroll
         for (int qt = 0; qt < 2; qt++) {
-            if (qrow[qt] >= a.n_q) continue;
+            if (qrow_e + 16 * qt >= a.n_q) continue;
 #pragma unroll
             for (int dt = 0; dt < 4; dt++)
 #pragma unroll
@@ -469,12 +476,13 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     const int hd = a.heads * 64;
 #pragma unroll
     for (int qt = 0; qt < 2; qt++) {
-        if (qrow[qt] >= a.n_q) continue;
+        const int qr = qrow_e + 16 * qt;
+        if (qr >= a.n_q) continue;
         const float inv = 1.0f / l_tot[qt];
         bf16_t* orow;
-        if (qrow[qt] < a.split) orow = static_cast<bf16_t*>(a.o) + ((size_t)b * a.split + qrow[qt]) * hd;
-        else orow = static_cast<bf16_t*>(a.o2) + ((size_t)b * (a.n_q - a.split) + (qrow[qt] - a.split)) * hd;
-        orow += h * 64 + 4 * q4;
+        if (qr < a.split) orow = static_cast<bf16_t*>(a.o) + ((size_t)b * a.split + qr) * hd;
+        else orow = static_cast<bf16_t*>(a.o2) + ((size_t)b * (a.n_q - a.split) + (qr - a.split)) * hd;
+        orow += h * 64 + 4 * q4_e;
 #pragma unroll
         for (int dt = 0; dt < 4; dt++) {
             bf16x4 ov = {(bf16_t)(o[dt][qt][0] * inv), (bf16_t)(o[dt][qt][1] * inv),

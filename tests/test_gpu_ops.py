@@ -266,8 +266,16 @@ def test_attention_prescaled_out_of_range_sums_start_over(hb, case):
     o1 = _prescaled(hb, q, k, v)
     got = host(o1)
     assert np.isfinite(got).all()
-    assert err(got, O.attention(q, k, v, scale=LN2)) < 1e-2
+    want = O.attention(q, k, v, scale=LN2)
+    assert err(got, want) < 1e-2
     assert torch.equal(o1, _prescaled(hb, q, k, v))
+    # the entry point that takes the scale (here ln 2: the same scores) tries sums without a reference maximum first
+    # as well, multiplying every score by scale x log2(e), and starts over in the same cases
+    o2 = torch.empty_like(o1)
+    hb.hyb_joint_attention(*(dev(a, torch.bfloat16) for a in (q, k, v)), o2, scale=LN2)
+    got2 = host(o2)
+    assert np.isfinite(got2).all()
+    assert err(got2, want) < 1e-2
 
 
 def test_attention_prescaled_split_parts_with_mixed_references(hb):
