@@ -215,6 +215,19 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
     constexpr bool GEGLU = EPI == EPI_GEGLU;
     [[maybe_unused]] const int q_cols = EPI == EPI_QKV && p.q_scale != 0.f ? p.heads * 64 : 0;   // columns of the q part that are scaled
     [[maybe_unused]] const float q_scale = p.q_scale;
+    // EPI_QKV: where the tile's first column and row lie (feature = (which, offset in q / k / v), row = (sample, token))
+    [[maybe_unused]] int qkv_which0 = 0, qkv_cc0 = 0, qkv_b0 = 0, qkv_t0 = 0;
+    [[maybe_unused]] bool qkv_steps = false;   // chunks reach their place by at most one step over each boundary
+    if constexpr (EPI == EPI_QKV) {
+        const int hd = p.heads * 64;
+        qkv_steps = hd >= BN && p.tokens >= BM;
+        if (qkv_steps) {
+            qkv_which0 = col0 / hd;
+            qkv_cc0 = col0 - qkv_which0 * hd;
+            qkv_b0 = row0 / p.tokens;
+            qkv_t0 = row0 - qkv_b0 * p.tokens;
+        }
+    }
     constexpr bool F32OUT = sizeof(OT) == 4 || GEGLU;   // GEGLU stages u and gate in fp32 and combines on the way out
     constexpr int NPASS = (F32OUT && TMW == 2) ? 2 : 1;   // a 128-token fp32 tile is staged in two 64-token halves
     constexpr int STRIDE = F32OUT ? OUT_STRIDE_F32 : OUT_STRIDE_B16;
@@ -354,10 +367,26 @@ __global__ __launch_bounds__(256, TMW == 2 ? 2 : 3) void gemm_mfma_kernel(GemmGr
             }
             const unsigned char* srcp = smem + trow * STRIDE + ch * 16;
             if constexpr (EPI == EPI_QKV) {
-                // feature f = (which, head, i); token row r = (sample b, token t): 8 features stay inside one head
+                // feature f = (which, head, i); token row r = (sample b, token t): 8 features stay inside one head.
+                // The divisions are taken once per tile, on its first column and row; a chunk adds its offset and steps
+                // over at most one boundary of each kind when a tile is no wider than q, k or v and no taller than a
+                // sample (otherwise every chunk divides).
                 const int hd = p.heads * 64;
-                const int which = f / hd, cc = f - which * hd, head = cc / 64, i0 = cc % 64;
-                const int b = r / p.tokens, t = r - b * p.tokens;
+                int which, cc, b, t;
+                if (qkv_steps) {
+                    which = qkv_which0;
+                    cc = qkv_cc0 + ch * CHUNK_ELEMS;
+                    if (cc >= hd) { cc -= hd; which++; }
+                    b = qkv_b0;
+                    t = qkv_t0 + pass * ROWS_PER_PASS + trow;
+                    if (t >= p.tokens) { t -= p.tokens; b++; }
+                } else {
+                    which = f / hd;
+                    cc = f - which * hd;
+                    b = r / p.tokens;
+                    t = r - b * p.tokens;
+                }
+                const int head = cc / 64, i0 = cc % 64;
                 OT* base = static_cast<OT*>(which == 0 ? p.q : (which == 1 ? p.k : p.v));
                 OT* dst = base + (((size_t)b * p.heads + head) * p.n_total + p.tok_offset + t) * 64 + i0;
                 *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(srcp);
