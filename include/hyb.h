@@ -132,7 +132,10 @@ int hyb_cfg_disc_euler_noalloc(const void* v_c, const void* v_u, const float* x,
  * o: device [batch, n_q, heads * head_dim] (heads merged, feature = head * head_dim + i).
  * For joint attention n_q = n_kv = n_img + n_txt with image tokens first; n_q != n_kv is
  * cross-attention.  scale <= 0 means 1 / sqrt(head_dim).  head_dim must be 64.
- * n_q == 0 or batch == 0 is a no-op; n_kv == 0 with n_q > 0 is HYB_ERR_SHAPE. */
+ * n_q == 0 or batch == 0 is a no-op; n_kv == 0 with n_q > 0 is HYB_ERR_SHAPE.
+ * The bf16 kernel first sums 2^(score * scale * log2 e) without a reference maximum; a workgroup (128 query rows)
+ * one of whose row sums leaves [2^-64, 2^64] starts over with a running maximum, so the result is the softmax
+ * for every finite input, and an input whose scaled scores exceed about +-44 takes up to twice as long. */
 int hyb_joint_attention(const void* q, const void* k, const void* v, void* o,
                         int batch, int heads, int n_q, int n_kv, int head_dim, float scale,
                         hyb_dtype dtype, void* stream);
@@ -152,10 +155,9 @@ size_t hyb_joint_attention_workspace_bytes(int batch, int heads, int n_q, hyb_dt
 /* The same attention (workspace form) for queries that already carry the softmax scale and the change of base:
  * q holds q * scale * log2(e), so that q k^T is the exponent of 2 and o = softmax_2(q k^T) v, which is
  * softmax(q_unscaled k^T * scale) v.  A producer that rounds q to bf16 anyway (hyb_block_forward's QKV
- * projection does this) folds the factor in before its one rounding and loses nothing.  The bf16 kernel
- * then first tries the sums without a reference maximum (P = 2^score, one instruction per score less, no row
- * maxima); a workgroup whose row sums leave [2^-64, 2^64] (scores of more than about +-50 in base 2) starts
- * over with the running-maximum form, so the result is defined for every finite input.  HYB_F32 inputs take the
+ * projection does this) folds the factor in before its one rounding and loses nothing.  The bf16 kernel's
+ * first attempt (sums without a reference maximum, see hyb_joint_attention) then needs no multiplication per
+ * score either: P = 2^score; the fallback for row sums outside [2^-64, 2^64] is the same.  HYB_F32 inputs take the
  * plain fp32 kernel with scale = ln 2.  Same shapes, workspace and error behaviour as hyb_joint_attention_ws
  * (Sec. 3 of the paper: the attention inside one evaluation of the denoiser). */
 int hyb_joint_attention_prescaled(const void* q, const void* k, const void* v, void* o,

@@ -171,13 +171,16 @@ def test_attention_running_maximum_schedules(hb, growth):
     """Scores that rise steadily along the key axis: the row maximum of every 64-key tile exceeds the previous
     one by `growth` (in base-2 exponent units), so the kernel's deferred rescaling (it only advances its running
     maximum when the tile maximum has grown by more than 2^8) sees growth below, just below and far above its
-    threshold; descending order (the first tile holds the maximum) rides along as the second head."""
+    threshold; descending order (the first tile holds the maximum) rides along as the second head.  All scores sit
+    2^80 above zero, so that the kernel's first attempt (sums without a reference maximum) is out of range for every
+    row and the loop with the running maximum is what produces the result."""
     B, H, N = 1, 2, 650                               # 10 full tiles + a ragged one
     rng = np.random.default_rng(77)
     q = np.zeros((B, H, N, 64), np.float32)
     k = np.zeros((B, H, N, 64), np.float32)
     q[..., 0] = 8.0
-    ramp = growth / 64.0 * np.arange(N) / (8.0 * 0.125 * 1.4426950408889634)    # score_j * log2(e) = growth * j / 64
+    # score_j * log2(e) = 80 + growth * j / 64
+    ramp = (80.0 + growth / 64.0 * np.arange(N)) / (8.0 * 0.125 * 1.4426950408889634)
     k[0, 0, :, 0] = ramp
     k[0, 1, :, 0] = ramp[::-1]
     q[..., 1:] = synth.round_bf16(0.05 * rng.standard_normal((B, H, N, 63)).astype(np.float32))
