@@ -67,8 +67,6 @@ constexpr float RESCALE_LOG2 = 8.0f;
 constexpr int PART_FLOATS = 36 * 256;       // per part of a split unit and thread: 32 accumulator values, 2 maxima, 2 normalisers
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef bf16x4 __attribute__((address_space(3)))* lds_bf16x4_ptr;
-typedef const void __attribute__((address_space(1)))* gptr_t;
 typedef void __attribute__((address_space(3)))* lptr_t;
 
 // One swizzle for both tiles: the 16-byte slot index of row r is XORed with (r & 6) | (r >> 3 & 1); the same for rows
@@ -180,15 +178,14 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
     }
     const int h = pair % a.heads, b = pair / a.heads;
     const size_t bh = (size_t)b * a.heads + h;
-    // the lane's two query rows (one per 16-query tile of the wave's 32)
-    int qrow[2];
+    // the lane's two query rows (one per 16-query tile of the wave's 32), clamped on load
     bf16x8 qf[2][2];   // [query tile][32-feature step]
     const bf16_t* kp = static_cast<const bf16_t*>(a.k) + bh * a.n_kv * 64;
     const bf16_t* vp = static_cast<const bf16_t*>(a.v) + bh * a.n_kv * 64;
 #pragma unroll
     for (int qt = 0; qt < 2; qt++) {
-        qrow[qt] = qb * BQ + wave * 32 + qt * 16 + l16;
-        const bf16_t* qp = static_cast<const bf16_t*>(a.q) + (bh * (a.q_stride ? a.q_stride : a.n_q) + min(qrow[qt], a.n_q - 1)) * 64;
+        const int qrow = qb * BQ + wave * 32 + qt * 16 + l16;
+        const bf16_t* qp = static_cast<const bf16_t*>(a.q) + (bh * (a.q_stride ? a.q_stride : a.n_q) + min(qrow, a.n_q - 1)) * 64;
 #pragma unroll
         for (int ks = 0; ks < 2; ks++) qf[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 32 + kq * 8);
     }
@@ -264,14 +261,18 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         __builtin_amdgcn_s_barrier();                      // ... everyone's; and the other buffer is free again
         if (t + 1 < t_end) issue(t + 1, BUF ^ 1);
 
+        // the other base addresses differ from kbase / vbase in bit 6 (K: the second 32-feature step) and bit 5 (V: the
+        // second 16-feature tile).  The leanest form of the tile (no reference maximum, no multiplication) has two
+        // registers to spare for them over the loop; the others make them here, one instruction each (asm, so that
+        // the compiler does not move them out of the loop)
+        unsigned kb1 = kbase ^ 64u, vb1 = vbase ^ 32u;
+        if constexpr (!(DIRECT && PRE)) {
+            asm volatile("v_xor_b32 %0, 64, %1" : "=v"(kb1) : "v"(kbase));
+            asm volatile("v_xor_b32 %0, 32, %1" : "=v"(vb1) : "v"(vbase));
+        }
         // S^T = K Q^T: eight accumulators (4 key tiles x 2 query tiles), two 32-feature steps each; the K fragments
         // (step ks, key tile kt: row 16 kt + l16, slot (4 ks + kq) ^ swz(row)) flow through a ring of four so that four
         // LDS reads are always in flight ahead of the MFMAs that need them.
-        // the other base addresses differ from these in bit 6 (K: the second 32-feature step) and bit 5 (V: the second
-        // 16-feature tile); they are made here, one instruction each, rather than kept in registers over the loop
-        unsigned kb1, vb1;
-        asm volatile("v_xor_b32 %0, 64, %1" : "=v"(kb1) : "v"(kbase));
-        asm volatile("v_xor_b32 %0, 32, %1" : "=v"(vb1) : "v"(vbase));
         auto k_frag = [&](int j) {
             const int ks = j >> 2, kt = j & 3;
             return *(const bf16x8 __attribute__((address_space(3)))*)((ks ? kb1 : kbase) + BUF_OFF + kt * 16 * ROWB);
