@@ -278,6 +278,10 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
             return *(const bf16x8 __attribute__((address_space(3)))*)((ks ? kb1 : kbase) + BUF_OFF + kt * 16 * ROWB);
         };
         bf16x8 ring[4];
+        // Wave priority: high while the wave feeds the MFMA pipe (both contractions, and across the tile boundary with its
+        // wait, barrier and copies), low during its softmax.  The four waves of a SIMD are in different phases; with equal
+        // priorities the vector instructions of one wave's softmax delay the MFMAs of another (-5 % kernel time).
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int j = 0; j < 4; j++) ring[j] = k_frag(j);
         f32x4 s[4][2];   // [key tile][query tile]: keys 16 kt + 4 q4 .. + 3 of query 16 qt + l16
@@ -318,6 +322,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
                 }
         }
         // the exponentiated scores of key tiles 2 ks, 2 ks + 1, rounded to bf16, are the B operand of 32-key step ks
+        __builtin_amdgcn_s_setprio(0);
         bf16x8 pb[2][2];   // [32-key step][query tile]
         if constexpr (DIRECT) {
 #pragma unroll
@@ -381,6 +386,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
             }
             v_frags<BUF>(vb2, vb3, vh[1]);
         }
+        __builtin_amdgcn_s_setprio(1);
         lds_wait<8>(vh[0], vf[0]);   // (the 8 reads of the other half may still be on their way)
 #pragma unroll
         for (int dd = 0; dd < 2; dd++)
