@@ -279,8 +279,8 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
         };
         bf16x8 ring[4];
         // Wave priority: high while the wave feeds the MFMA pipe (both contractions, and across the tile boundary with its
-        // wait, barrier and copies), low during its softmax.  The four waves of a SIMD are in different phases; with equal
-        // priorities the vector instructions of one wave's softmax delay the MFMAs of another (-5 % kernel time).
+        // wait, barrier and copies), low during the exponentials of its softmax.  The four waves of a SIMD are in different
+        // phases; with equal priorities the exponentials of one wave delay the MFMAs of another (-8 % kernel time).
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int j = 0; j < 4; j++) ring[j] = k_frag(j);
@@ -330,8 +330,18 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
                 for (int qt = 0; qt < 2; qt++)
 #pragma unroll
-                    for (int i = 0; i < 4; i++)
-                        pb[kt >> 1][qt][4 * (kt & 1) + i] = (bf16_t)__builtin_amdgcn_exp2f(PRE ? s[kt][qt][i] : s[kt][qt][i] * c);
+                    for (int i = 0; i < 4; i++) s[kt][qt][i] = __builtin_amdgcn_exp2f(PRE ? s[kt][qt][i] : s[kt][qt][i] * c);
+            // only the exponentials run at low priority: the conversions (and later the dot products) fill the gaps between
+            // this wave's own MFMAs better than they yield to other waves (the results pass through an empty asm
+            // statement, which keeps the conversions behind the change of priority)
+            asm volatile("" : "+v"(s[0][0]), "+v"(s[0][1]), "+v"(s[1][0]), "+v"(s[1][1]), "+v"(s[2][0]), "+v"(s[2][1]), "+v"(s[3][0]), "+v"(s[3][1]));
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+                for (int qt = 0; qt < 2; qt++)
+#pragma unroll
+                    for (int i = 0; i < 4; i++) pb[kt >> 1][qt][4 * (kt & 1) + i] = (bf16_t)s[kt][qt][i];
         } else {
             // v_max3_f32 directly: fmaxf() makes the compiler canonicalise every MFMA output first (one extra
             // multiply per score), which costs more than the maxima themselves
