@@ -322,6 +322,13 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
                 }
         }
         // the exponentiated scores of key tiles 2 ks, 2 ks + 1, rounded to bf16, are the B operand of 32-key step ks
+        if constexpr (DIRECT && !PRE) {   // the multiplications still at high priority
+#pragma unroll
+            for (int kt = 0; kt < 4; kt++)
+#pragma unroll
+                for (int qt = 0; qt < 2; qt++) s[kt][qt] *= c;
+            asm volatile("" : "+v"(s[0][0]), "+v"(s[0][1]), "+v"(s[1][0]), "+v"(s[1][1]), "+v"(s[2][0]), "+v"(s[2][1]), "+v"(s[3][0]), "+v"(s[3][1]));
+        }
         __builtin_amdgcn_s_setprio(0);
         bf16x8 pb[2][2];   // [32-key step][query tile]
         if constexpr (DIRECT) {
@@ -330,7 +337,7 @@ __global__ __launch_bounds__(256, 4) void attention_mfma_kernel(AttnArgs a) {
 #pragma unroll
                 for (int qt = 0; qt < 2; qt++)
 #pragma unroll
-                    for (int i = 0; i < 4; i++) s[kt][qt][i] = __builtin_amdgcn_exp2f(PRE ? s[kt][qt][i] : s[kt][qt][i] * c);
+                    for (int i = 0; i < 4; i++) s[kt][qt][i] = __builtin_amdgcn_exp2f(s[kt][qt][i]);
             // only the exponentials run at low priority: the conversions (and later the dot products) fill the gaps between
             // this wave's own MFMAs better than they yield to other waves (the results pass through an empty asm
             // statement, which keeps the conversions behind the change of priority)
