@@ -24,6 +24,9 @@
 // points at 4 features of key (i / 4) and receives feature (i) of 4 consecutive keys.
 // The K fragments of a tile flow through a ring of four reads that run ahead of the MFMAs; the V^T
 // fragments of the first 32 output features are requested before the softmax and used after it.
+// The four waves of a SIMD belong to four workgroups and are in different phases of their tiles; a wave lowers its
+// priority (s_setprio) for the 32 exponentials of a tile and keeps it high for everything else, so that one wave's
+// exponentials do not hold up another's MFMAs.
 //
 // Softmax runs in fp32 with exp2.  A workgroup first takes all its key tiles with reference 0: P = 2^(c score),
 // c = scale x log2(e): no row maxima, no exchange between lanes, no test for a grown maximum.  With prescaled
