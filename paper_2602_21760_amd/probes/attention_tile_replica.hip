@@ -40,12 +40,14 @@ constexpr int PAIRS = 64;                  // pairs in the global buffer (each 2
 
 __device__ __forceinline__ int swz_v(int r) { return ((r >> 1) & 1) * 4; }
 
-enum : int { F_LDS = 1, F_ORDER = 2, F_BARRIER = 4, F_COPY = 8, F_NO_EXP = 16, F_SMALL = 32 };
+enum : int { F_LDS = 1, F_ORDER = 2, F_BARRIER = 4, F_COPY = 8, F_NO_EXP = 16, F_SMALL = 32, F_PRIO = 64 };
 
 // flags: see the enum; blockDim = 256 (F_BARRIER: one workgroup of 4 waves, several per CU) or 256 x waves per SIMD
 template <int FLAGS>
 __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const unsigned char* kv, int random_regs) {
     constexpr bool LDS = FLAGS & F_LDS, ORDER = FLAGS & F_ORDER, BAR = FLAGS & F_BARRIER, COPY = FLAGS & F_COPY, NO_EXP = FLAGS & F_NO_EXP;
+    constexpr bool PRIO = (FLAGS & F_PRIO) && (FLAGS & F_SMALL) && (FLAGS & F_LDS);   // the kernel's wave priorities (with its
+                                                 // order of requests: the second half of the V^T fragments after the softmax)
     constexpr bool SMALL = FLAGS & F_SMALL;      // the same fragments multiplied by twice as many v_mfma_f32_16x16x32_bf16 (same multiply-adds)
     __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];      // two buffers of a K and a V tile
     for (int i = threadIdx.x; i < 4 * TILE / 4; i += blockDim.x) reinterpret_cast<unsigned*>(smem)[i] = reinterpret_cast<const unsigned*>(kv)[i];
@@ -108,6 +110,7 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
         if constexpr (SMALL)
             for (int d = 0; d < 8; d++)
                 for (int i = 0; i < 4; i++) s4[d][i] = 0.f;
+        if constexpr (PRIO) __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             bf16x8 kf = a[j & 3];
@@ -122,28 +125,47 @@ __global__ __launch_bounds__(1024) void tile_kernel(float* out, int n, const uns
         }
         if (ORDER) __builtin_amdgcn_sched_barrier(0);
         bf16x4 vh[2][2][2][2];
+        auto v_request = [&](int d) {
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int hf = 0; hf < 2; hf++) {
+                    const int off = (kt * 32 + hf * 16) * 128;
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[d][kt][hf][0]) : "v"(vbase[d] + boff), "i"(off));
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[d][kt][hf][1]) : "v"(vbase[d] + boff), "i"(off + 8 * 128));
+                }
+        };
         if (LDS) {
-#pragma unroll
-            for (int d = 0; d < 2; d++)
-#pragma unroll
-                for (int kt = 0; kt < 2; kt++)
-#pragma unroll
-                    for (int hf = 0; hf < 2; hf++) {
-                        const int off = (kt * 32 + hf * 16) * 128;
-                        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[d][kt][hf][0]) : "v"(vbase[d] + boff), "i"(off));
-                        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(vh[d][kt][hf][1]) : "v"(vbase[d] + boff), "i"(off + 8 * 128));
-                    }
+            v_request(0);
+            if constexpr (!PRIO) v_request(1);
         }
         bf16x8 pb[2][2];
+        if constexpr (PRIO) {
+            __builtin_amdgcn_s_setprio(0);
 #pragma unroll
-        for (int kt = 0; kt < 2; kt++)
+            for (int d = 0; d < 8; d++)
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
-                float sc;
-                if constexpr (SMALL) sc = s4[4 * kt + i / 4][i % 4];
-                else sc = s[kt][i];
-                pb[kt][i / 8][i % 8] = NO_EXP ? (bf16_t)sc : (bf16_t)__builtin_amdgcn_exp2f(sc);
-            }
+                for (int i = 0; i < 4; i++) s4[d][i] = __builtin_amdgcn_exp2f(s4[d][i]);
+            // (the exponentials are taken before the priority goes up again)
+            asm volatile("" : "+v"(s4[0]), "+v"(s4[1]), "+v"(s4[2]), "+v"(s4[3]), "+v"(s4[4]), "+v"(s4[5]), "+v"(s4[6]), "+v"(s4[7]));
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) pb[kt][i / 8][i % 8] = (bf16_t)s4[4 * kt + i / 4][i % 4];
+            asm volatile("" : "+v"(pb[0][0]), "+v"(pb[0][1]), "+v"(pb[1][0]), "+v"(pb[1][1]));
+            v_request(1);
+        } else {
+#pragma unroll
+            for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+                for (int i = 0; i < 16; i++) {
+                    float sc;
+                    if constexpr (SMALL) sc = s4[4 * kt + i / 4][i % 4];
+                    else sc = s[kt][i];
+                    pb[kt][i / 8][i % 8] = NO_EXP ? (bf16_t)sc : (bf16_t)__builtin_amdgcn_exp2f(sc);
+                }
+        }
         if (ORDER) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int d = 0; d < 2; d++)
@@ -318,13 +340,16 @@ int main() {
     // the complete tile with either MFMA form, random operands (still resident), 4 waves per SIMD: measured in turn, three
     // times over, since the granted clock drifts over milliseconds; median
     {
-        float ms[2][3];
+        float ms[4][3];
         for (int pass = 0; pass < 3; pass++) {
             ms[0][pass] = run<F_LDS | F_ORDER | F_BARRIER | F_COPY>(out, n, kv, 1, 4, cus);
             ms[1][pass] = run<F_LDS | F_ORDER | F_BARRIER | F_COPY | F_SMALL>(out, n, kv, 1, 4, cus);
+            ms[2][pass] = run<F_LDS | F_BARRIER | F_COPY | F_SMALL>(out, n, kv, 1, 4, cus);
+            ms[3][pass] = run<F_LDS | F_BARRIER | F_COPY | F_SMALL | F_PRIO>(out, n, kv, 1, 4, cus);
         }
-        const char* names[2] = {"complete tile, 32x32x16 MFMAs (median of 3, in turn)", "complete tile, 16x16x32 MFMAs (median of 3, in turn)"};
-        for (int v = 0; v < 2; v++) {
+        const char* names[4] = {"complete tile, 32x32x16 MFMAs (median of 3, in turn)", "complete tile, 16x16x32 MFMAs (median of 3, in turn)",
+                                "complete tile, 16x16x32 MFMAs, phases not held in order", "... wave priority low during the exponentials only"};
+        for (int v = 0; v < 4; v++) {
             const float a = ms[v][0], b = ms[v][1], c = ms[v][2];
             const float med = a > b ? (b > c ? b : (a > c ? c : a)) : (a > c ? a : (b > c ? c : b));
             printf("| random | %s | 4 | %.3f | %.1f | %.0f |\n", names[v], med, med * 1e6 / ((double)n * 4), 16.0 * 32768.0 * 4.0 * cus * n * 4 / (med * 1e-3) * 1e-12);
